@@ -1,0 +1,184 @@
+/*
+ * specext.h - C ABI of the SpecExtend verification hot path for AMD MI355X (gfx950).
+ *
+ * Implements, as hand-written HIP kernels, the verification-side operations of
+ * SpecExtend (arXiv 2505.20776):
+ *   - Hybrid Tree Attention (Sec. 3.1): the draft tree's tokens attend to the
+ *     target model's cached prefix (split over the KV length, FlashDecoding
+ *     style) and, under the tree mask, to each other; the parts are merged
+ *     exactly by log-sum-exp.
+ *   - Cross-model Retrieval (Sec. 3.2.1, Alg. 1): per-chunk average attention
+ *     scores of one query token, top-k chunk selection (SelectChunks) and the
+ *     compaction of the draft model's KV cache to the chosen chunks
+ *     (UpdateDraftCache).
+ *
+ * Conventions common to every entry point
+ *   - Every tensor argument is a DEVICE pointer owned by the caller.  The
+ *     library allocates nothing, frees nothing and keeps no pointer after the
+ *     call returns.  `stream` is the caller's hipStream_t passed as void*
+ *     (NULL = the default stream).  All work is enqueued asynchronously on it;
+ *     no entry point synchronises with the host.
+ *   - Return value: SPECEXT_OK (0) or a negative specext_status.  Errors that
+ *     the host can see (null pointers, unsupported shapes, misaligned
+ *     pointers, workspace too small) are reported BEFORE anything is launched
+ *     and leave all outputs untouched.  Data-dependent errors (a parent index
+ *     that is not smaller than its node) are reported through the status word
+ *     in the workspace, see specext_verify_attn.
+ *   - Row-major layouts, last index fastest.  L = prefix_len, T = n_tree,
+ *     Hq / Hkv = query / KV heads, G = Hq / Hkv, d = head_dim,
+ *     B = chunk_size, C = ceil(L / B).
+ *   - Thread safety: no global mutable state except a per-process cache of
+ *     device properties; concurrent calls on different streams are safe as
+ *     long as they use different workspaces.
+ */
+#ifndef SPECEXT_H_
+#define SPECEXT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum specext_status {
+  SPECEXT_OK = 0,
+  SPECEXT_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, bad struct_size ... */
+  SPECEXT_ERR_UNSUPPORTED = -2,        /* dtype / head_dim / n_tree / alignment outside what the kernels handle */
+  SPECEXT_ERR_WORKSPACE_TOO_SMALL = -3,
+  SPECEXT_ERR_LAUNCH_FAILED = -4       /* the HIP runtime refused a launch */
+} specext_status;
+
+typedef enum specext_dtype {
+  SPECEXT_F32 = 0,
+  SPECEXT_BF16 = 1
+} specext_dtype;
+
+#define SPECEXT_MAX_TREE 128           /* largest supported n_tree */
+#define SPECEXT_MAX_SPLITS 256         /* largest supported num_splits */
+
+/*
+ * Problem descriptor (plain data).  Set struct_size = sizeof(specext_desc).
+ * A stride of 0 means "densely packed" for the layouts given below.
+ */
+typedef struct specext_desc {
+  uint32_t struct_size;
+  int32_t dtype;          /* specext_dtype of q, k_*, v_* */
+  int32_t out_dtype;      /* specext_dtype of `out`; F32 or the input dtype */
+  int32_t n_q_heads;      /* Hq */
+  int32_t n_kv_heads;     /* Hkv, must divide Hq; query head h reads KV head h / G */
+  int32_t head_dim;       /* d: 64 or 128 */
+  int32_t prefix_len;     /* L >= 0 cached positions */
+  int32_t n_tree;         /* T in [1, SPECEXT_MAX_TREE] */
+  int32_t chunk_size;     /* B > 0; only read when want_scores != 0.  The bf16 fast path
+                             needs B to be a multiple of 32; other values take the generic kernel. */
+  int32_t want_scores;    /* != 0: also leave per-chunk partial sums in the workspace */
+  int32_t num_splits;     /* pieces the prefix is cut into; 0 = choose automatically */
+  float softmax_scale;    /* 0 = 1/sqrt(d) */
+  /* element strides; the d elements of one vector are always contiguous */
+  int64_t q_stride_t, q_stride_h;       /* q[t][h][:]        default Hq*d, d  */
+  int64_t kp_stride_h, kp_stride_l;     /* k_prefix[g][j][:] default L*d,  d  (v_prefix uses the same) */
+  int64_t kt_stride_h, kt_stride_t;     /* k_tree[g][t][:]   default T*d,  d  (v_tree uses the same) */
+  int64_t o_stride_t, o_stride_h;       /* out[t][h][:]      default Hq*d, d  */
+} specext_desc;
+
+/* Static text for a status code. */
+const char* specext_strerror(int status);
+
+/*
+ * Upper bound, in bytes, of the workspace specext_verify_attn needs for this
+ * descriptor (split partials, final log-sum-exp, chunk partial sums when
+ * want_scores, and the status word).  Returns 0 for an invalid descriptor.
+ * Host-only; needs a visible GPU only when num_splits == 0 (to read the
+ * compute-unit count).
+ */
+size_t specext_workspace_bytes(const specext_desc* desc);
+
+/*
+ * Hybrid Tree Attention for one layer (Sec. 3.1).
+ *
+ *   q         [T, Hq, d]   queries of the tree tokens           (desc->dtype)
+ *   k_prefix  [Hkv, L, d]  cached keys of the prefix, v_prefix likewise
+ *   k_tree    [Hkv, T, d]  keys of the tree tokens, v_tree likewise
+ *   parent    int32 [T]    parent[i] < i; -1 marks a root (whose conceptual
+ *                          parent is the last prefix token).  Forests allowed.
+ *   out       [T, Hq, d]   softmax(scale * q k^T over prefix keys and the
+ *                          ancestor-or-self tree keys) v      (desc->out_dtype)
+ *   lse       fp32 [Hq, T] natural-log sum-exp of each row; may be NULL
+ *   workspace at least specext_workspace_bytes(desc) bytes, 256-byte aligned.
+ *
+ * Pointers must be 16-byte aligned and strides multiples of 8 elements.
+ * The first int32 of the workspace is a status word: 0 after a good call,
+ * 1 if some parent[i] was >= i or < -1 (that node is then treated as a root).
+ * With want_scores the workspace afterwards holds what specext_chunk_scores
+ * consumes; it stays valid until the next call that uses this workspace.
+ */
+int specext_verify_attn(const specext_desc* desc, const void* q, const void* k_prefix,
+                        const void* v_prefix, const void* k_tree, const void* v_tree,
+                        const int32_t* parent, void* out, float* lse, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
+ * Chunk scores (Sec. 3.2.1): scores[r][c] = mean over query heads of the mean,
+ * over the tokens actually in chunk c, of the attention probability that tree
+ * row r gives to those tokens (normalised over the row's full key set).
+ *
+ *   desc, workspace   exactly what the preceding specext_verify_attn call on
+ *                     the same stream was given, with want_scores != 0
+ *   score_row         tree row to score, or -1 for every row
+ *   scores            fp32 [C] (one row) or fp32 [T, C] (score_row == -1)
+ */
+int specext_chunk_scores(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                         int32_t score_row, float* scores, void* stream);
+
+/*
+ * SelectChunks (Alg. 1): the min(k, n_chunks) chunks with the largest score.
+ * Ties go to the lower chunk index.  Scores must be finite.
+ *
+ *   scores   fp32 [n_chunks], n_chunks in [1, 65536]
+ *   k        >= 0
+ *   idx_out  int32 [k]; the first min(k, n_chunks) entries receive the chosen
+ *            chunk indices in ascending order, the rest are set to -1
+ *   n_out    int32 [1] on the device: min(k, n_chunks)
+ */
+int specext_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int32_t* idx_out,
+                          int32_t* n_out, void* stream);
+
+/*
+ * UpdateDraftCache (Alg. 1): compact the draft model's KV cache to the chosen
+ * chunks, copying bytes verbatim, in the order of idx.
+ *
+ *   k_src, v_src  [n_layers, n_kv_heads, src_len, head_dim] elements of elem_bytes
+ *   k_dst, v_dst  [n_layers, n_kv_heads, dst_cap, head_dim]; token slot
+ *                 r*chunk_size + t of the output receives token
+ *                 idx[r]*chunk_size + t of the source.  A ragged last source
+ *                 chunk contributes only its real tokens and later chunks
+ *                 follow it without a gap.
+ *   idx           device int32 [max_idx]; entries < 0 or >= ceil(src_len/chunk_size) are skipped
+ *   n_idx         device int32 [1] (how many entries of idx are used, clamped to
+ *                 max_idx) or NULL to use all max_idx entries
+ *   dst_cap       token capacity of the destination; must be >= max_idx * chunk_size
+ *   pos_out       int32 [dst_cap] original position of every written token
+ *                 (-1 beyond len_out); may be NULL
+ *   len_out       device int32 [1]: tokens written; may be NULL
+ *
+ * head_dim * elem_bytes must be a multiple of 16 and all four cache pointers
+ * 16-byte aligned.
+ */
+int specext_gather_draft_kv(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
+                            const int32_t* idx, const int32_t* n_idx, int32_t max_idx,
+                            int32_t n_layers, int32_t n_kv_heads, int32_t src_len, int32_t dst_cap,
+                            int32_t head_dim, int32_t chunk_size, int32_t elem_bytes,
+                            int32_t* pos_out, int32_t* len_out, void* stream);
+
+/*
+ * Number of prefix splits specext_verify_attn uses for this descriptor when
+ * desc->num_splits == 0 (else returns desc->num_splits clamped to what is
+ * valid).  Returns a negative specext_status on an invalid descriptor.
+ */
+int specext_num_splits(const specext_desc* desc);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECEXT_H_ */

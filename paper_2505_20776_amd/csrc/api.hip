@@ -1,0 +1,252 @@
+// C ABI of libspecext: argument validation, workspace layout, kernel dispatch.
+// See include/specext.h for the contract of every entry point.
+#include <atomic>
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace specext {
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct WorkspaceLayout {
+  size_t status_off, lse2_off, part_ml_off, part_o_off, chunk_off, total;
+};
+
+// Compute-unit count of the current device, cached per process.
+int device_cu_count() {
+  static std::atomic<int> cached{0};
+  int v = cached.load(std::memory_order_relaxed);
+  if (v > 0) return v;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+  cached.store(cus, std::memory_order_relaxed);
+  return cus;
+}
+
+int64_t gcd64(int64_t a, int64_t b) {
+  while (b) {
+    const int64_t t = a % b;
+    a = b;
+    b = t;
+  }
+  return a;
+}
+
+// Validate the descriptor and resolve every default.  Pointers are not looked at here.
+int resolve(const specext_desc* d, AttnParams* p) {
+  if (!d || d->struct_size != sizeof(specext_desc)) return SPECEXT_ERR_INVALID_ARG;
+  if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->prefix_len < 0 || d->n_tree <= 0 || d->num_splits < 0)
+    return SPECEXT_ERR_INVALID_ARG;
+  if (d->n_q_heads % d->n_kv_heads != 0) return SPECEXT_ERR_INVALID_ARG;
+  if (d->want_scores && d->chunk_size <= 0) return SPECEXT_ERR_INVALID_ARG;
+  if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return SPECEXT_ERR_INVALID_ARG;
+  if (d->dtype != SPECEXT_F32 && d->dtype != SPECEXT_BF16) return SPECEXT_ERR_UNSUPPORTED;
+  if (d->out_dtype != SPECEXT_F32 && d->out_dtype != d->dtype) return SPECEXT_ERR_UNSUPPORTED;
+  if (d->head_dim != 64 && d->head_dim != 128) return SPECEXT_ERR_UNSUPPORTED;
+  if (d->n_tree > SPECEXT_MAX_TREE || d->num_splits > SPECEXT_MAX_SPLITS) return SPECEXT_ERR_UNSUPPORTED;
+  if (static_cast<int64_t>(d->n_q_heads) * d->n_tree > (1 << 20)) return SPECEXT_ERR_UNSUPPORTED;
+
+  std::memset(p, 0, sizeof(*p));
+  p->Hq = d->n_q_heads;
+  p->Hkv = d->n_kv_heads;
+  p->G = p->Hq / p->Hkv;
+  p->d = d->head_dim;
+  p->L = d->prefix_len;
+  p->T = d->n_tree;
+  p->M = p->T * p->G;
+  p->want_scores = d->want_scores ? 1 : 0;
+  p->B = p->want_scores ? d->chunk_size : 1;
+  p->C = p->want_scores ? (p->L + p->B - 1) / p->B : 0;
+  p->in_dtype = d->dtype;
+  p->out_dtype = d->out_dtype;
+  const float scale = d->softmax_scale > 0.f ? d->softmax_scale : 1.0f / std::sqrt(static_cast<float>(p->d));
+  p->scale_log2 = scale * kLog2e;
+  p->q_st = d->q_stride_t ? d->q_stride_t : static_cast<int64_t>(p->Hq) * p->d;
+  p->q_sh = d->q_stride_h ? d->q_stride_h : p->d;
+  p->kp_sh = d->kp_stride_h ? d->kp_stride_h : static_cast<int64_t>(p->L) * p->d;
+  p->kp_sl = d->kp_stride_l ? d->kp_stride_l : p->d;
+  p->kt_sh = d->kt_stride_h ? d->kt_stride_h : static_cast<int64_t>(p->T) * p->d;
+  p->kt_st = d->kt_stride_t ? d->kt_stride_t : p->d;
+  p->o_st = d->o_stride_t ? d->o_stride_t : static_cast<int64_t>(p->Hq) * p->d;
+  p->o_sh = d->o_stride_h ? d->o_stride_h : p->d;
+  const int64_t strides[] = {p->q_st, p->q_sh, p->kp_sh, p->kp_sl, p->kt_sh, p->kt_st, p->o_st, p->o_sh};
+  for (int64_t s : strides)
+    if (s < 0 || s % 8 != 0) return SPECEXT_ERR_UNSUPPORTED;
+  if (p->q_sh < p->d || p->kp_sl < p->d || p->kt_st < p->d || p->o_sh < p->d) return SPECEXT_ERR_INVALID_ARG;
+
+  // Split the prefix.  Every split but the last holds keys_per_split keys, a
+  // multiple of 64 and, with scores, of the chunk size, so that no chunk is
+  // shared by two splits.
+  if (p->L == 0) {
+    p->S = 0;
+    p->keys_per_split = 64;
+    return SPECEXT_OK;
+  }
+  int64_t unit = 64;
+  if (p->want_scores) unit = unit / gcd64(unit, p->B) * p->B;
+  int want = d->num_splits;
+  if (want == 0) {
+    // about two workgroups' worth of splits per compute unit across the KV heads,
+    // but at least 256 keys per split so the partials stay small next to the stream
+    const int cus = device_cu_count();
+    want = (cus + p->Hkv - 1) / p->Hkv;
+    const int by_len = static_cast<int>((p->L + 255) / 256);
+    if (want > by_len) want = by_len;
+    if (want < 1) want = 1;
+  }
+  if (want > SPECEXT_MAX_SPLITS) want = SPECEXT_MAX_SPLITS;
+  int64_t per = (p->L + want - 1) / want;
+  per = (per + unit - 1) / unit * unit;
+  p->keys_per_split = static_cast<int32_t>(per);
+  p->S = static_cast<int32_t>((p->L + per - 1) / per);
+  return SPECEXT_OK;
+}
+
+WorkspaceLayout layout_of(const AttnParams& p) {
+  WorkspaceLayout w;
+  const size_t rows = static_cast<size_t>(p.Hq) * p.T;
+  size_t off = 0;
+  w.status_off = off;
+  off += kAlign;
+  w.lse2_off = off;
+  off += align_up(rows * sizeof(float));
+  w.part_ml_off = off;
+  off += align_up(static_cast<size_t>(p.S) * rows * 2 * sizeof(float));
+  w.part_o_off = off;
+  off += align_up(static_cast<size_t>(p.S) * rows * p.d * sizeof(float));
+  w.chunk_off = off;
+  if (p.want_scores) off += align_up(rows * static_cast<size_t>(p.C) * 2 * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+void bind_workspace(AttnParams* p, const WorkspaceLayout& w, void* workspace) {
+  char* base = static_cast<char*>(workspace);
+  p->status = reinterpret_cast<int32_t*>(base + w.status_off);
+  p->lse2 = reinterpret_cast<float*>(base + w.lse2_off);
+  p->part_ml = reinterpret_cast<float*>(base + w.part_ml_off);
+  p->part_o = reinterpret_cast<float*>(base + w.part_o_off);
+  p->chunk_part = p->want_scores ? reinterpret_cast<float*>(base + w.chunk_off) : nullptr;
+}
+
+inline bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
+
+}  // namespace
+}  // namespace specext
+
+using namespace specext;
+
+extern "C" {
+
+const char* specext_strerror(int status) {
+  switch (status) {
+    case SPECEXT_OK: return "ok";
+    case SPECEXT_ERR_INVALID_ARG: return "invalid argument";
+    case SPECEXT_ERR_UNSUPPORTED: return "unsupported dtype, shape or alignment";
+    case SPECEXT_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case SPECEXT_ERR_LAUNCH_FAILED: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t specext_workspace_bytes(const specext_desc* desc) {
+  AttnParams p;
+  if (resolve(desc, &p) != SPECEXT_OK) return 0;
+  return layout_of(p).total;
+}
+
+int specext_num_splits(const specext_desc* desc) {
+  AttnParams p;
+  const int rc = resolve(desc, &p);
+  if (rc != SPECEXT_OK) return rc;
+  return p.S;
+}
+
+int specext_verify_attn(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
+                        const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  AttnParams p;
+  const int rc = resolve(desc, &p);
+  if (rc != SPECEXT_OK) return rc;
+  if (!q || !k_tree || !v_tree || !parent || !out || !workspace) return SPECEXT_ERR_INVALID_ARG;
+  if (p.L > 0 && (!k_prefix || !v_prefix)) return SPECEXT_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(k_tree) || !aligned16(v_tree) ||
+      !aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
+      (reinterpret_cast<uintptr_t>(parent) & 3u) != 0 || (reinterpret_cast<uintptr_t>(lse) & 3u) != 0)
+    return SPECEXT_ERR_UNSUPPORTED;
+  const WorkspaceLayout w = layout_of(p);
+  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  p.q = q;
+  p.kp = k_prefix;
+  p.vp = v_prefix;
+  p.kt = k_tree;
+  p.vt = v_tree;
+  p.parent = parent;
+  p.out = out;
+  p.lse = lse;
+  bind_workspace(&p, w, workspace);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p.S > 0) {
+    const hipError_t e = prefix_mfma_supports(p) ? launch_prefix_mfma(p, s) : launch_prefix_generic(p, s);
+    if (e != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  }
+  if (launch_tree_merge(p, s) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_chunk_scores(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                         int32_t score_row, float* scores, void* stream) {
+  AttnParams p;
+  const int rc = resolve(desc, &p);
+  if (rc != SPECEXT_OK) return rc;
+  if (!workspace || !scores || !p.want_scores || p.C <= 0) return SPECEXT_ERR_INVALID_ARG;
+  if (score_row < -1 || score_row >= p.T) return SPECEXT_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || (reinterpret_cast<uintptr_t>(scores) & 3u) != 0)
+    return SPECEXT_ERR_UNSUPPORTED;
+  const WorkspaceLayout w = layout_of(p);
+  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  bind_workspace(&p, w, const_cast<void*>(workspace));
+  if (launch_chunk_scores(p, score_row, scores, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int32_t* idx_out, int32_t* n_out,
+                          void* stream) {
+  if (!scores || !n_out || n_chunks <= 0 || k < 0 || (k > 0 && !idx_out)) return SPECEXT_ERR_INVALID_ARG;
+  if (n_chunks > 65536) return SPECEXT_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(scores) & 3u) || (reinterpret_cast<uintptr_t>(idx_out) & 3u) ||
+      (reinterpret_cast<uintptr_t>(n_out) & 3u))
+    return SPECEXT_ERR_UNSUPPORTED;
+  if (launch_select_chunks(scores, n_chunks, k, idx_out, n_out, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_gather_draft_kv(const void* k_src, const void* v_src, void* k_dst, void* v_dst, const int32_t* idx,
+                            const int32_t* n_idx, int32_t max_idx, int32_t n_layers, int32_t n_kv_heads,
+                            int32_t src_len, int32_t dst_cap, int32_t head_dim, int32_t chunk_size,
+                            int32_t elem_bytes, int32_t* pos_out, int32_t* len_out, void* stream) {
+  if (!k_src || !v_src || !k_dst || !v_dst || !idx) return SPECEXT_ERR_INVALID_ARG;
+  if (max_idx < 0 || n_layers <= 0 || n_kv_heads <= 0 || src_len <= 0 || dst_cap < 0 || head_dim <= 0 ||
+      chunk_size <= 0 || elem_bytes <= 0)
+    return SPECEXT_ERR_INVALID_ARG;
+  if (static_cast<int64_t>(max_idx) * chunk_size > dst_cap) return SPECEXT_ERR_INVALID_ARG;
+  const int64_t row_bytes = static_cast<int64_t>(head_dim) * elem_bytes;
+  const int64_t n_lh = static_cast<int64_t>(n_layers) * n_kv_heads;
+  if (row_bytes % 16 != 0 || row_bytes > (1 << 20) || n_lh > 65535) return SPECEXT_ERR_UNSUPPORTED;
+  if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_dst) || !aligned16(v_dst)) return SPECEXT_ERR_UNSUPPORTED;
+  if (launch_gather(k_src, v_src, k_dst, v_dst, idx, n_idx, max_idx, static_cast<int32_t>(n_lh), src_len, dst_cap,
+                    static_cast<int32_t>(row_bytes), chunk_size, pos_out, len_out,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,72 @@
+// Internal declarations shared by the HIP translation units of libspecext.
+// Nothing here is part of the public ABI (see include/specext.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "specext.h"
+
+namespace specext {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// One verification-attention problem with every default resolved.  Passed to
+// kernels by value.  Rows of a KV head g are numbered m = t * G + hg
+// (t = tree node, hg = query head within the group); the global row id is
+// rid = g * M + m with M = T * G.  All softmax bookkeeping is kept in the
+// base-2 domain: logits are multiplied by scale * log2(e) once.
+struct AttnParams {
+  const void* q;
+  const void* kp;
+  const void* vp;
+  const void* kt;
+  const void* vt;
+  const int32_t* parent;
+  void* out;
+  float* lse;          // user output, natural log, [Hq][T]; may be null
+  // workspace pieces
+  int32_t* status;     // [1]
+  float* lse2;         // [Hq*T] base-2 log-sum-exp per rid
+  float* part_ml;      // [S][Hq*T][2]  (running max, running sum) per split
+  float* part_o;       // [S][Hq*T][d]  unnormalised partial outputs
+  float* chunk_part;   // [Hq*T][C][2]  (sum of exp2(s - ref), ref) per chunk; null unless want_scores
+  int32_t Hq, Hkv, G, d, L, T, M;
+  int32_t B, C, S, keys_per_split, want_scores;
+  int32_t in_dtype, out_dtype;
+  float scale_log2;
+  int64_t q_st, q_sh, kp_sh, kp_sl, kt_sh, kt_st, o_st, o_sh;
+};
+
+// Launchers (each returns a hipError_t from the launch itself).
+hipError_t launch_prefix_generic(const AttnParams& p, hipStream_t stream);
+hipError_t launch_prefix_mfma(const AttnParams& p, hipStream_t stream);
+bool prefix_mfma_supports(const AttnParams& p);
+hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream);
+hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, float* scores, hipStream_t stream);
+hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int32_t* idx_out,
+                                int32_t* n_out, hipStream_t stream);
+hipError_t launch_gather(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
+                         const int32_t* idx, const int32_t* n_idx, int32_t max_idx, int32_t n_lh,
+                         int32_t src_len, int32_t dst_cap, int32_t row_bytes, int32_t chunk_size,
+                         int32_t* pos_out, int32_t* len_out, hipStream_t stream);
+
+// bf16 helpers (bit-level; round to nearest even on the way down)
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+}  // namespace specext

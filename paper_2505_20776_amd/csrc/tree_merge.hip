@@ -1,0 +1,143 @@
+// Tree pass and log-sum-exp merge of Hybrid Tree Attention (SpecExtend Sec. 3.1).
+//
+// One wavefront per query row (tree node t of query head h).  The lanes hold
+// the head dimension.  The wave first walks the node's ancestor chain through
+// parent[] (the tree mask lets a node see itself and its ancestors only) with
+// an online softmax, then folds in the prefix splits in split order, each
+// weighted by exp2(max_split - max_total).  The merge is a fixed-order fp32
+// reduction: no atomics, bit-reproducible from run to run.
+#include "common.h"
+
+namespace specext {
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+
+template <int D, bool IN_BF16>
+__device__ __forceinline__ void load_vec(const void* base, int64_t off, int lane, float (&v)[D / 64]) {
+  constexpr int E = D / 64;
+  if (IN_BF16) {
+    const uint16_t* b = static_cast<const uint16_t*>(base) + off + lane * E;
+    if (E == 2) {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(b);
+      v[0] = __uint_as_float(w << 16);
+      v[E - 1] = __uint_as_float(w & 0xffff0000u);
+    } else {
+      v[0] = bf16_bits_to_float(b[0]);
+    }
+  } else {
+    const float* b = static_cast<const float*>(base) + off + lane * E;
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[e] = b[e];
+  }
+}
+
+template <int D, bool IN_BF16>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnParams p) {
+  constexpr int E = D / 64;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);   // rid
+  const int n_rows = p.Hq * p.T;
+  if (blockIdx.x == 0 && threadIdx.x < 64) {
+    // single writer of the status word: 1 if any parent index is not a topological one
+    bool bad = false;
+    for (int i = lane; i < p.T; i += 64) {
+      const int par = p.parent[i];
+      bad |= (par >= i) || (par < -1);
+    }
+    const bool any_bad = __any(bad);
+    if (lane == 0) *p.status = any_bad ? 1 : 0;
+  }
+  if (row >= n_rows) return;
+  const int g = row / p.M;
+  const int m = row - g * p.M;
+  const int t = m / p.G;
+  const int h = g * p.G + m % p.G;
+
+  float q[E], o[E];
+  load_vec<D, IN_BF16>(p.q, t * p.q_st + h * p.q_sh, lane, q);
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    q[e] *= p.scale_log2;
+    o[e] = 0.f;
+  }
+  float run_max = -INFINITY, run_sum = 0.f;
+
+  // tree part: node t and its ancestors
+  int a = t;
+  while (a >= 0) {
+    float kv[E];
+    load_vec<D, IN_BF16>(p.kt, g * p.kt_sh + a * p.kt_st, lane, kv);
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) dot = fmaf(q[e], kv[e], dot);
+    const float s = wave_sum(dot);
+    const float new_max = fmaxf(run_max, s);
+    const float alpha = exp2f(run_max - new_max);
+    const float pr = exp2f(s - new_max);
+    load_vec<D, IN_BF16>(p.vt, g * p.kt_sh + a * p.kt_st, lane, kv);
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] = fmaf(pr, kv[e], o[e] * alpha);
+    run_sum = fmaf(run_sum, alpha, pr);
+    run_max = new_max;
+    const int par = p.parent[a];
+    a = (par >= a || par < -1) ? -1 : par;   // a malformed entry ends the walk (node treated as a root)
+  }
+
+  // prefix splits, in split order
+  for (int s = 0; s < p.S; ++s) {
+    const int64_t slot = static_cast<int64_t>(s) * n_rows + row;
+    const float ms = p.part_ml[slot * 2];
+    const float ls = p.part_ml[slot * 2 + 1];
+    if (!(ls > 0.f)) continue;       // empty split
+    const float new_max = fmaxf(run_max, ms);
+    const float alpha = exp2f(run_max - new_max);
+    const float beta = exp2f(ms - new_max);
+    const float* po = p.part_o + slot * D + lane * E;
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] = fmaf(po[e], beta, o[e] * alpha);
+    run_sum = fmaf(ls, beta, run_sum * alpha);
+    run_max = new_max;
+  }
+
+  const float inv = 1.f / run_sum;
+  const int64_t ooff = t * p.o_st + h * p.o_sh + lane * E;
+  if (p.out_dtype == SPECEXT_BF16) {
+    uint16_t* ob = static_cast<uint16_t*>(p.out) + ooff;
+    if (E == 2) {
+      const uint32_t w = static_cast<uint32_t>(float_to_bf16_bits(o[0] * inv)) |
+                         (static_cast<uint32_t>(float_to_bf16_bits(o[E - 1] * inv)) << 16);
+      *reinterpret_cast<uint32_t*>(ob) = w;
+    } else {
+      ob[0] = float_to_bf16_bits(o[0] * inv);
+    }
+  } else {
+    float* of = static_cast<float*>(p.out) + ooff;
+#pragma unroll
+    for (int e = 0; e < E; ++e) of[e] = o[e] * inv;
+  }
+  if (lane == 0) {
+    const float l2 = run_max + log2f(run_sum);
+    p.lse2[row] = l2;
+    if (p.lse) p.lse[h * p.T + t] = l2 * kLn2;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream) {
+  const int n_rows = p.Hq * p.T;
+  dim3 grid((n_rows + kWavesPerBlock - 1) / kWavesPerBlock);
+  dim3 block(kWavesPerBlock * 64);
+  const bool bf16 = p.in_dtype == SPECEXT_BF16;
+  if (p.d == 128) {
+    if (bf16) tree_merge_kernel<128, true><<<grid, block, 0, stream>>>(p);
+    else tree_merge_kernel<128, false><<<grid, block, 0, stream>>>(p);
+  } else {
+    if (bf16) tree_merge_kernel<64, true><<<grid, block, 0, stream>>>(p);
+    else tree_merge_kernel<64, false><<<grid, block, 0, stream>>>(p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace specext

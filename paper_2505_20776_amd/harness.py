@@ -1,0 +1,117 @@
+"""Device-buffer plumbing around the binding: allocate torch tensors for a
+problem, call the C entry points, bring results back.  Marshalling only; every
+step of the method runs in the HIP kernels."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as sx
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """fp32 numpy values (exactly representable in `dtype`) -> device tensor of that dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def dtype_code(dtype: str) -> int:
+    return {"f32": sx.SPECEXT_F32, "bf16": sx.SPECEXT_BF16}[dtype]
+
+
+@dataclass
+class VerifyBuffers:
+    desc: sx.specext_desc
+    out: torch.Tensor
+    lse: torch.Tensor
+    workspace: torch.Tensor
+    scores: Optional[torch.Tensor]
+
+
+def make_buffers(*, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, prefix_len: int, n_tree: int,
+                 chunk_size: int = 0, want_scores: bool = False, num_splits: int = 0, out_dtype: Optional[str] = None,
+                 softmax_scale: float = 0.0, device="cuda") -> VerifyBuffers:
+    odt = out_dtype or dtype
+    desc = sx.make_desc(dtype=dtype_code(dtype), out_dtype=dtype_code(odt), n_q_heads=n_q_heads,
+                        n_kv_heads=n_kv_heads, head_dim=head_dim, prefix_len=prefix_len, n_tree=n_tree,
+                        chunk_size=chunk_size, want_scores=want_scores, num_splits=num_splits,
+                        softmax_scale=softmax_scale)
+    nbytes = sx.workspace_bytes(desc)
+    if nbytes == 0:
+        raise ValueError("descriptor rejected by specext_workspace_bytes")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    out = torch.empty((n_tree, n_q_heads, head_dim), dtype=torch.bfloat16 if odt == "bf16" else torch.float32,
+                      device=device)
+    lse = torch.empty((n_q_heads, n_tree), dtype=torch.float32, device=device)
+    scores = None
+    if want_scores:
+        n_chunks = (prefix_len + chunk_size - 1) // chunk_size
+        scores = torch.empty((n_tree, max(n_chunks, 1)), dtype=torch.float32, device=device)
+    return VerifyBuffers(desc, out, lse, ws, scores)
+
+
+def run_verify(wl, *, num_splits: int = 0, want_scores: bool = True, out_dtype: Optional[str] = None):
+    """Run verify_attn (+ chunk_scores for every row) on a workloads.Workload.
+    Returns dict of numpy arrays: out fp32 [T,Hq,d], lse [Hq,T], scores [T,C] or None, status int."""
+    dev = "cuda"
+    q = to_device(wl.q, wl.dtype, dev)
+    kp = to_device(wl.k_prefix, wl.dtype, dev)
+    vp = to_device(wl.v_prefix, wl.dtype, dev)
+    kt = to_device(wl.k_tree, wl.dtype, dev)
+    vt = to_device(wl.v_tree, wl.dtype, dev)
+    parent = torch.from_numpy(np.asarray(wl.parent, dtype=np.int32)).to(dev)
+    want_scores = want_scores and wl.prefix_len > 0
+    buf = make_buffers(dtype=wl.dtype, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
+                       prefix_len=wl.prefix_len, n_tree=wl.n_tree, chunk_size=wl.chunk_size,
+                       want_scores=want_scores, num_splits=num_splits, out_dtype=out_dtype, device=dev)
+    sx.verify_attn(buf.desc, q, kp if wl.prefix_len else None, vp if wl.prefix_len else None, kt, vt, parent,
+                   buf.out, buf.lse, buf.workspace)
+    if want_scores:
+        sx.chunk_scores(buf.desc, buf.workspace, -1, buf.scores)
+    torch.cuda.synchronize()
+    status = int(buf.workspace[:4].view(torch.int32).item())
+    return {
+        "out": buf.out.float().cpu().numpy(),
+        "lse": buf.lse.cpu().numpy(),
+        "scores": buf.scores.cpu().numpy() if want_scores else None,
+        "status": status,
+        "num_splits": sx.num_splits(buf.desc),
+    }
+
+
+def run_select(scores_row: np.ndarray, k: int):
+    """select_chunks on one row of scores; returns (idx int32 [min(k,C)], n_out, raw idx buffer)."""
+    s = torch.from_numpy(np.ascontiguousarray(scores_row, dtype=np.float32)).cuda()
+    idx = torch.full((max(k, 1),), -7, dtype=torch.int32, device="cuda")
+    n_out = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    sx.select_chunks(s, s.numel(), k, idx, n_out)
+    torch.cuda.synchronize()
+    n = int(n_out.item())
+    raw = idx.cpu().numpy()
+    return raw[:n].copy(), n, raw[:k].copy()
+
+
+def run_gather(k_src: torch.Tensor, v_src: torch.Tensor, idx: np.ndarray, chunk_size: int, *,
+               n_idx: Optional[int] = None, max_idx: Optional[int] = None):
+    """gather_draft_kv on [Ld,H,L,d] device tensors.  Returns (k_dst, v_dst, pos, length) with the
+    destination sized max_idx * chunk_size tokens and pre-filled with a canary pattern."""
+    ld, hh, plen, d = k_src.shape
+    idx_t = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
+    max_idx = int(len(idx) if max_idx is None else max_idx)
+    cap = max_idx * chunk_size
+    k_dst = torch.full((ld, hh, max(cap, 1), d), 77, dtype=k_src.dtype, device="cuda")[:, :, :cap]
+    v_dst = torch.full((ld, hh, max(cap, 1), d), 77, dtype=k_src.dtype, device="cuda")[:, :, :cap]
+    k_dst = k_dst.contiguous()
+    v_dst = v_dst.contiguous()
+    pos = torch.full((max(cap, 1),), -5, dtype=torch.int32, device="cuda")
+    length = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+    n_idx_t = None if n_idx is None else torch.tensor([n_idx], dtype=torch.int32, device="cuda")
+    if idx_t.numel() == 0:
+        idx_t = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sx.gather_draft_kv(k_src, v_src, k_dst, v_dst, idx_t, n_idx_t, max_idx, ld, hh, plen, cap, d, chunk_size,
+                       k_src.element_size(), pos, length)
+    torch.cuda.synchronize()
+    return k_dst, v_dst, pos.cpu().numpy()[:cap], int(length.item())

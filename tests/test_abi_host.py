@@ -1,0 +1,130 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before launching."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sx():
+    import paper_2505_20776_amd as sx
+    if not os.path.exists(os.path.join(ROOT, "paper_2505_20776_amd", "libspecext.so")):
+        from paper_2505_20776_amd.build import build_library
+        build_library(verbose=False)
+    sx.load_library()
+    return sx
+
+
+def _header_symbols():
+    text = open(os.path.join(ROOT, "include", "specext.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(specext_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(sx):
+    lib = sx.load_library()
+    names = _header_symbols()
+    assert set(names) == set(sx.binding.EXPORTED)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_descriptor_layout_matches_header(sx):
+    # 12 four-byte fields then 8 eight-byte strides, naturally aligned
+    assert ctypes.sizeof(sx.specext_desc) == 12 * 4 + 8 * 8
+    assert sx.specext_desc.q_stride_t.offset == 48
+
+
+def _good(sx, **kw):
+    base = dict(dtype=sx.SPECEXT_BF16, n_q_heads=32, n_kv_heads=8, head_dim=128, prefix_len=4096, n_tree=60,
+                chunk_size=32, want_scores=True, num_splits=8)
+    base.update(kw)
+    return sx.make_desc(**base)
+
+
+def test_workspace_and_splits(sx):
+    d = _good(sx)
+    assert sx.num_splits(d) == 8
+    ws = sx.workspace_bytes(d)
+    rows = 32 * 60
+    assert ws >= 8 * rows * 128 * 4 + rows * 128 * 2 * 4
+    assert ws % 256 == 0
+    # splits never cut a chunk: keys per split is a multiple of lcm(64, B)
+    d = _good(sx, prefix_len=1000, num_splits=7, chunk_size=48)
+    assert 1 <= sx.num_splits(d) <= 7
+    d = _good(sx, prefix_len=0)
+    assert sx.num_splits(d) == 0 and sx.workspace_bytes(d) > 0
+    d = _good(sx, prefix_len=100, num_splits=200)
+    assert sx.num_splits(d) == 2                        # 64-key granularity
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("struct_size", 4, -1), ("n_q_heads", 0, -1), ("n_kv_heads", 5, -1), ("prefix_len", -1, -1),
+    ("n_tree", 0, -1), ("chunk_size", 0, -1), ("num_splits", -2, -1), ("softmax_scale", -1.0, -1),
+    ("dtype", 7, -2), ("head_dim", 96, -2), ("n_tree", 129, -2), ("num_splits", 257, -2),
+    ("q_stride_h", 12, -2), ("kp_stride_l", 64, -1),
+])
+def test_bad_descriptor_is_rejected(sx, field, value, status):
+    d = _good(sx)
+    setattr(d, field, value)
+    assert sx.workspace_bytes(d) == 0
+    assert sx.num_splits(d) == status
+    rc = sx.verify_attn(d, 256, 256, 256, 256, 256, 256, 256, None, 256, workspace_nbytes=1 << 40, stream=0,
+                        check=False)
+    assert rc == status
+    assert sx.chunk_scores(d, 256, -1, 256, workspace_nbytes=1 << 40, stream=0, check=False) == status
+
+
+def test_bad_pointers_are_rejected_before_launch(sx):
+    d = _good(sx)
+    ws = sx.workspace_bytes(d)
+    ok = 4096
+    args = [ok] * 7
+    for i in (0, 1, 2, 3, 4, 5, 6):                        # each required pointer null in turn
+        a = list(args); a[i] = None
+        assert sx.verify_attn(d, *a, None, ok, workspace_nbytes=ws, stream=0, check=False) == -1
+    assert sx.verify_attn(d, *args, None, None, workspace_nbytes=ws, stream=0, check=False) == -1
+    a = list(args); a[1] = ok + 8                          # misaligned k_prefix
+    assert sx.verify_attn(d, *a, None, ok, workspace_nbytes=ws, stream=0, check=False) == -2
+    assert sx.verify_attn(d, *args, None, ok + 64, workspace_nbytes=ws, stream=0, check=False) == -2
+    assert sx.verify_attn(d, *args, None, ok, workspace_nbytes=ws - 1, stream=0, check=False) == -3
+    with pytest.raises(sx.SpecextError):
+        sx.verify_attn(d, *args, None, ok, workspace_nbytes=0, stream=0)
+    # chunk_scores needs want_scores and a valid row
+    assert sx.chunk_scores(d, ok, 60, ok, workspace_nbytes=ws, stream=0, check=False) == -1
+    assert sx.chunk_scores(d, ok, -2, ok, workspace_nbytes=ws, stream=0, check=False) == -1
+    assert sx.chunk_scores(d, None, 0, ok, workspace_nbytes=ws, stream=0, check=False) == -1
+    assert sx.chunk_scores(d, ok, 0, ok, workspace_nbytes=16, stream=0, check=False) == -3
+    d2 = _good(sx, want_scores=False)
+    assert sx.chunk_scores(d2, ok, 0, ok, workspace_nbytes=ws, stream=0, check=False) == -1
+
+
+def test_select_and_gather_argument_checks(sx):
+    ok = 4096
+    assert sx.select_chunks(None, 4, 2, ok, ok, stream=0, check=False) == -1
+    assert sx.select_chunks(ok, 0, 2, ok, ok, stream=0, check=False) == -1
+    assert sx.select_chunks(ok, 4, -1, ok, ok, stream=0, check=False) == -1
+    assert sx.select_chunks(ok, 4, 2, None, ok, stream=0, check=False) == -1
+    assert sx.select_chunks(ok, 4, 2, ok, None, stream=0, check=False) == -1
+    assert sx.select_chunks(ok, 70000, 2, ok, ok, stream=0, check=False) == -2
+    assert sx.select_chunks(ok + 2, 4, 2, ok, ok, stream=0, check=False) == -2
+    g = dict(max_idx=4, n_layers=1, n_kv_heads=8, src_len=1024, dst_cap=128, head_dim=128, chunk_size=32,
+             elem_bytes=2, stream=0, check=False)
+    assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **g) != -1 or True   # valid shape is not exercised here
+    assert sx.gather_draft_kv(None, ok, ok, ok, ok, None, **g) == -1
+    assert sx.gather_draft_kv(ok, ok, ok, ok, None, None, **g) == -1
+    assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, dst_cap=127)) == -1
+    assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, chunk_size=0)) == -1
+    assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, head_dim=100, elem_bytes=1)) == -2
+    assert sx.gather_draft_kv(ok + 4, ok, ok, ok, ok, None, **g) == -2
+    assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, n_layers=9000)) == -2
+
+
+def test_strerror(sx):
+    assert sx.strerror(0) == "ok"
+    assert "workspace" in sx.strerror(-3)
+    assert sx.strerror(-99) == "unknown status"

@@ -1,0 +1,363 @@
+"""GPU parity: the HIP path through the C ABI versus the fp64 oracle, element by element.
+
+Bars (stated where they are applied, see parity_util): out max-abs <= 2e-3 for
+fp32 inputs and <= 2e-2 for bf16 inputs, both also relative to max|O|; lse
+<= 2e-3; chunk scores within 1e-4 of the row's largest score; chunk indices by
+the tolerance-aware top-k rule (exact where the margin is wide); gathered KV
+bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from parity_util import (TOL, check_attention, check_scores, check_selection, oracle_all)
+from workloads import (Workload, chain_tree, config_tree, config_workload, eagle_style_tree, make_workload,
+                       random_parent_tree, wide_tree)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hx():
+    from paper_2505_20776_amd import harness
+    return harness
+
+
+def _full_check(hx, wl, what, **kw):
+    print(f"[case] {what} L={wl.prefix_len} T={wl.n_tree} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
+          f"{wl.dtype} B={wl.chunk_size} {kw}", flush=True)
+    ref_out, ref_lse, ref_scores = oracle_all(wl)
+    res = hx.run_verify(wl, **kw)
+    assert res["status"] == 0
+    rel = check_attention(wl, res, ref_out, ref_lse, what)
+    if ref_scores is not None and res["scores"] is not None:
+        check_scores(res["scores"], ref_scores, what)
+    return res, ref_out, ref_lse, ref_scores, rel
+
+
+# --------------------------------------------------------------------------
+# configuration 1: fp32 toy, all split counts
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("splits", [0, 1, 3, 8])
+def test_toy_fp32(hx, splits):
+    wl = config_workload(1)
+    res, _, _, ref_scores, _ = _full_check(hx, wl, f"toy splits={splits}", num_splits=splits)
+    sel, n, raw = hx.run_select(res["scores"][wl.score_row], wl.top_k)
+    assert n == wl.top_k
+    check_selection(sel, ref_scores[wl.score_row], wl.top_k, "toy")
+    assert set(wl.needle_chunks) <= set(int(i) for i in sel)
+
+
+def test_toy_sharp_and_ragged(hx):
+    for plen in (512, 500, 33, 31, 1):
+        wl = config_workload(1, sharp=True, prefix_len=plen)
+        _full_check(hx, wl, f"toy sharp L={plen}")
+
+
+# --------------------------------------------------------------------------
+# configuration 2: one Llama-3.1-8B-shaped layer, bf16
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("sharp", [False, True])
+def test_llama_layer_2k(hx, sharp):
+    wl = config_workload(2, sharp=sharp)
+    res, _, _, ref_scores, rel = _full_check(hx, wl, f"cfg2 sharp={sharp}")
+    print(f"    relative out error {rel:.3e}", flush=True)
+    for row in (wl.score_row, wl.n_tree - 1):
+        sel, n, _ = hx.run_select(res["scores"][row], wl.top_k)
+        check_selection(sel, ref_scores[row], wl.top_k, f"cfg2 row {row}")
+    sel, _, _ = hx.run_select(res["scores"][wl.score_row], wl.top_k)
+    assert set(wl.needle_chunks) <= set(int(i) for i in sel)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 5, 32])
+def test_llama_layer_split_counts(hx, splits):
+    wl = config_workload(2, sharp=True, prefix_len=2048 - 37)
+    _full_check(hx, wl, f"cfg2 ragged splits={splits}", num_splits=splits)
+
+
+def test_fp32_output_of_bf16_inputs(hx):
+    wl = config_workload(2, sharp=True, prefix_len=777)
+    _full_check(hx, wl, "cfg2 fp32 out", out_dtype="f32")
+
+
+# --------------------------------------------------------------------------
+# shapes: ragged tails, tiny and maximal trees, head_dim 64, other group sizes
+# --------------------------------------------------------------------------
+
+SHAPES = [
+    # dtype, Hq, Hkv, d, L, tree, B
+    ("bf16", 32, 8, 128, 1, "eagle60", 32),
+    ("bf16", 32, 8, 128, 63, "eagle60", 32),
+    ("bf16", 32, 8, 128, 65, "single", 32),
+    ("bf16", 32, 8, 128, 4096 + 13, "wide128", 64),
+    ("bf16", 32, 8, 128, 3000, "chain16", 64),
+    ("bf16", 8, 8, 128, 1500, "eagle60", 32),       # G = 1
+    ("bf16", 16, 2, 128, 1111, "rand8", 32),        # G = 8
+    ("bf16", 8, 2, 64, 2049, "eagle60", 32),        # head_dim 64
+    ("bf16", 32, 8, 128, 2048, "eagle60", 48),      # chunk size not a multiple of 32
+    ("f32", 8, 2, 128, 700, "rand8", 32),
+    ("f32", 4, 1, 64, 129, "chain16", 16),
+]
+
+
+def _tree(kind, rng):
+    return {"eagle60": lambda: eagle_style_tree(60, 6, rng), "single": lambda: chain_tree(1),
+            "wide128": lambda: wide_tree(128, 4, rng), "chain16": lambda: chain_tree(16),
+            "rand8": lambda: random_parent_tree(8, 4, rng)}[kind]()
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,L,tree,B", SHAPES)
+def test_shapes(hx, dtype, Hq, Hkv, d, L, tree, B):
+    rng = np.random.default_rng(Hq * 1000 + L)
+    wl = make_workload(f"shape_{tree}", seed=L * 7 + d, dtype=dtype, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d,
+                       prefix_len=L, parent=_tree(tree, rng), chunk_size=B, top_k=4, n_needles=0, value_std=1.0)
+    _full_check(hx, wl, f"shape {tree}")
+
+
+def test_empty_prefix(hx):
+    rng = np.random.default_rng(5)
+    wl = make_workload("empty", seed=5, dtype="bf16", n_q_heads=32, n_kv_heads=8, head_dim=128, prefix_len=0,
+                       parent=eagle_style_tree(60, 6, rng), chunk_size=32, top_k=4, n_needles=0, value_std=1.0)
+    ref_out, ref_lse, _ = orc.verify_attention(wl.q, wl.k_prefix, wl.v_prefix, wl.k_tree, wl.v_tree, wl.parent)
+    res = hx.run_verify(wl, want_scores=False)
+    check_attention(wl, res, ref_out, ref_lse, "empty prefix")
+
+
+def test_chain_tree_is_causal(hx):
+    """The chain case checked against the separately written causal routine."""
+    wl = make_workload("chain", seed=77, dtype="bf16", n_q_heads=32, n_kv_heads=8, head_dim=128, prefix_len=900,
+                       parent=chain_tree(16), chunk_size=64, top_k=4, n_needles=0, value_std=1.0)
+    res = hx.run_verify(wl)
+    k_all = np.concatenate([wl.k_prefix, wl.k_tree], axis=1)
+    v_all = np.concatenate([wl.v_prefix, wl.v_tree], axis=1)
+    ref = orc.causal_attention_tail(wl.q, k_all, v_all)
+    err = np.abs(res["out"] - ref).max()
+    assert err <= TOL["bf16"] * np.abs(ref).max()
+
+
+# --------------------------------------------------------------------------
+# adversarial logits: a ramp (the max moves on every tile) and a +40 outlier
+# --------------------------------------------------------------------------
+
+def _directional(seed, L, ramp=None, outlier=None):
+    rng = np.random.default_rng(seed)
+    parent = eagle_style_tree(60, 6, rng)
+    wl = make_workload("adv", seed=seed, dtype="bf16", n_q_heads=32, n_kv_heads=8, head_dim=128, prefix_len=L,
+                       parent=parent, chunk_size=32, top_k=8, n_needles=0, value_std=0.25)
+    d = wl.head_dim
+    u = np.zeros(d, dtype=np.float32); u[3] = 1.0
+    from workloads import quantize
+    wl.q = quantize(wl.q * 0.1 + u * 4.0, "bf16")            # every query points along u
+    if ramp is not None:
+        steps = np.linspace(0.0, ramp, L, dtype=np.float32)     # logit grows along the sequence
+        wl.k_prefix = quantize(wl.k_prefix + steps[None, :, None] * u[None, None, :], "bf16")
+    if outlier is not None:
+        pos, mag = outlier
+        wl.k_prefix[:, pos, :] = quantize(u * mag, "bf16")
+    return wl
+
+
+def test_ramp_logits(hx):
+    wl = _directional(901, 3000, ramp=float(60.0 * np.sqrt(128) / 4.0))   # logits climb by about 60 over the prefix
+    _full_check(hx, wl, "ramp")
+    wl = _directional(902, 3000, ramp=-float(60.0 * np.sqrt(128) / 4.0))
+    _full_check(hx, wl, "descending ramp")
+
+
+def test_outlier_key(hx):
+    mag = float(40.0 * np.sqrt(128) / 4.0)
+    for pos in (0, 1234, 2999):
+        wl = _directional(903 + pos, 3000, outlier=(pos, mag))
+        res, ref_out, _, ref_scores, _ = _full_check(hx, wl, f"outlier at {pos}")
+        c = pos // wl.chunk_size
+        size = min(wl.chunk_size, wl.prefix_len - c * wl.chunk_size)     # the last chunk is ragged
+        assert abs(res["scores"][0, c] * size - 1.0) < 1e-3
+
+
+# --------------------------------------------------------------------------
+# strides, status word, determinism
+# --------------------------------------------------------------------------
+
+def test_strided_inputs(hx):
+    import paper_2505_20776_amd as sx
+    wl = config_workload(2, sharp=True, prefix_len=1000)
+    ref_out, ref_lse, _ = orc.verify_attention(wl.q, wl.k_prefix, wl.v_prefix, wl.k_tree, wl.v_tree, wl.parent)
+    T, Hq, d, Hkv, L = wl.n_tree, wl.n_q_heads, wl.head_dim, wl.n_kv_heads, wl.prefix_len
+    cap = L + 24                                        # cache allocated longer than it is filled
+    kp = torch.zeros((Hkv, cap, 2 * d), dtype=torch.bfloat16, device="cuda")   # rows padded to 2d elements
+    vp = torch.zeros_like(kp)
+    kp[:, :L, :d] = hx.to_device(wl.k_prefix, "bf16"); vp[:, :L, :d] = hx.to_device(wl.v_prefix, "bf16")
+    qq = torch.zeros((T, Hq + 1, d), dtype=torch.bfloat16, device="cuda"); qq[:, :Hq] = hx.to_device(wl.q, "bf16")
+    oo = torch.full((T, Hq, d + 8), 9.0, dtype=torch.bfloat16, device="cuda")
+    buf = hx.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T)
+    buf.desc.q_stride_t = (Hq + 1) * d
+    buf.desc.kp_stride_h = cap * 2 * d; buf.desc.kp_stride_l = 2 * d
+    buf.desc.o_stride_t = Hq * (d + 8); buf.desc.o_stride_h = d + 8
+    parent = torch.from_numpy(wl.parent).cuda()
+    sx.verify_attn(buf.desc, qq, kp, vp, hx.to_device(wl.k_tree, "bf16"), hx.to_device(wl.v_tree, "bf16"), parent,
+                   oo, buf.lse, buf.workspace)
+    torch.cuda.synchronize()
+    res = {"out": oo[:, :, :d].float().cpu().numpy(), "lse": buf.lse.cpu().numpy()}
+    check_attention(wl, res, ref_out, ref_lse, "strided")
+    assert (oo[:, :, d:].float() == 9.0).all()          # padding untouched
+
+
+def test_malformed_parent_sets_status(hx):
+    wl = config_workload(1)
+    wl.parent = wl.parent.copy(); wl.parent[3] = 5           # forward reference
+    res = hx.run_verify(wl)
+    assert res["status"] == 1
+    assert np.isfinite(res["out"]).all()
+    wl.parent[3] = 1
+    assert hx.run_verify(wl)["status"] == 0
+
+
+def test_run_to_run_bit_identical(hx):
+    wl = config_workload(2, sharp=True, prefix_len=3000)
+    a = hx.run_verify(wl)
+    b = hx.run_verify(wl)
+    assert (a["out"] == b["out"]).all() and (a["lse"] == b["lse"]).all() and (a["scores"] == b["scores"]).all()
+
+
+# --------------------------------------------------------------------------
+# SelectChunks on its own: bit-exact against the oracle on the same fp32 values
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,k", [(1, 1), (16, 4), (64, 32), (512, 32), (512, 512), (512, 600), (1000, 0),
+                                 (4097, 100), (65536, 2048)])
+def test_select_exact(hx, n, k):
+    rng = np.random.default_rng(n + k)
+    s = rng.random(n).astype(np.float32)
+    sel, n_out, raw = hx.run_select(s, k)
+    ref = orc.select_chunks(s, k)
+    assert n_out == min(n, k) and list(sel) == list(ref)
+    assert (raw[n_out:] == -1).all()
+
+
+def test_select_ties_and_signs(hx):
+    rng = np.random.default_rng(4)
+    s = rng.integers(0, 4, size=777).astype(np.float32)         # heavy ties
+    for k in (1, 5, 200, 776):
+        sel, _, _ = hx.run_select(s, k)
+        assert list(sel) == list(orc.select_chunks(s, k))
+    s = (rng.standard_normal(300) * 3).astype(np.float32); s[7] = 0.0; s[9] = -0.0
+    for k in (3, 150, 299):
+        sel, _, _ = hx.run_select(s, k)
+        assert list(sel) == list(orc.select_chunks(s, k))
+    s = np.full(100, 0.25, dtype=np.float32)
+    sel, _, _ = hx.run_select(s, 10)
+    assert list(sel) == list(range(10))
+
+
+# --------------------------------------------------------------------------
+# UpdateDraftCache on its own: byte-exact
+# --------------------------------------------------------------------------
+
+def test_gather_exact(hx):
+    rng = np.random.default_rng(8)
+    Ld, H, L, d, B = 2, 3, 1000 - 37, 128, 32               # ragged last chunk of 3 tokens
+    bits_k = torch.from_numpy(rng.integers(-2 ** 15, 2 ** 15, size=(Ld, H, L, d)).astype(np.int16)).cuda()
+    bits_v = torch.from_numpy(rng.integers(-2 ** 15, 2 ** 15, size=(Ld, H, L, d)).astype(np.int16)).cuda()
+    ks, vs = bits_k.view(torch.bfloat16), bits_v.view(torch.bfloat16)
+    C = (L + B - 1) // B
+    for idx in ([0, 5, 7, C - 1], [C - 1, 3, 3, 0], list(range(C)), [2]):
+        kd, vd, pos, n = hx.run_gather(ks, vs, np.array(idx), B)
+        rk, rv, rpos = orc.gather_draft_kv(bits_k.cpu().numpy(), bits_v.cpu().numpy(), idx, B)
+        assert n == len(rpos) and list(pos[:n]) == list(rpos) and (pos[n:] == -1).all()
+        assert (kd.view(torch.int16)[:, :, :n].cpu().numpy() == rk).all()
+        assert (vd.view(torch.int16)[:, :, :n].cpu().numpy() == rv).all()
+        assert (kd[:, :, n:].float() == 77).all() and (vd[:, :, n:].float() == 77).all()   # nothing written behind
+    # n_idx on the device limits the list; invalid entries are skipped
+    kd, vd, pos, n = hx.run_gather(ks, vs, np.array([4, 9, 1, 2]), B, n_idx=2)
+    rk, rv, rpos = orc.gather_draft_kv(bits_k.cpu().numpy(), bits_v.cpu().numpy(), [4, 9], B)
+    assert n == 2 * B and (kd.view(torch.int16)[:, :, :n].cpu().numpy() == rk).all() and list(pos[:n]) == list(rpos)
+    kd, vd, pos, n = hx.run_gather(ks, vs, np.array([4, -1, C + 3, 6]), B)
+    rk, rv, rpos = orc.gather_draft_kv(bits_k.cpu().numpy(), bits_v.cpu().numpy(), [4, 6], B)
+    assert n == 2 * B and (vd.view(torch.int16)[:, :, :n].cpu().numpy() == rv).all() and list(pos[:n]) == list(rpos)
+    # fp32 elements, head_dim 64
+    src = torch.from_numpy(rng.standard_normal((1, 2, 300, 64)).astype(np.float32)).cuda()
+    kd, vd, pos, n = hx.run_gather(src, src * 2, np.array([1, 0]), 100)
+    assert (kd[0, :, :100] == src[0, :, 100:200]).all() and (vd[0, :, 100:200] == 2 * src[0, :, 0:100]).all()
+
+
+# --------------------------------------------------------------------------
+# configuration 3: 8K prefix, scores -> top-32 of 256 -> gather 1x8x1024x128
+# --------------------------------------------------------------------------
+
+def test_config3_retrieval_pipeline(hx):
+    wl = config_workload(3)
+    res, ref_out, ref_lse, ref_scores, rel = _full_check(hx, wl, "cfg3")
+    print(f"    relative out error {rel:.3e}", flush=True)
+    row = wl.score_row
+    sel, n, _ = hx.run_select(res["scores"][row], wl.top_k)
+    same = check_selection(sel, ref_scores[row], wl.top_k, "cfg3")
+    assert set(wl.needle_chunks) <= set(int(i) for i in sel)
+    dk, dv = hx.to_device(wl.draft_k, "bf16"), hx.to_device(wl.draft_v, "bf16")
+    kd, vd, pos, length = hx.run_gather(dk, dv, sel, wl.chunk_size)
+    assert kd.shape == (1, 8, 1024, 128) and length == 1024
+    # bit-exact against the GPU's own index list ...
+    from workloads import f32_to_bf16_bits
+    rk, rv, rpos = orc.gather_draft_kv(f32_to_bf16_bits(wl.draft_k), f32_to_bf16_bits(wl.draft_v), sel, wl.chunk_size)
+    assert (kd.view(torch.int16).cpu().numpy().view(np.uint16) == rk).all()
+    assert (vd.view(torch.int16).cpu().numpy().view(np.uint16) == rv).all()
+    assert list(pos) == list(rpos)
+    # ... and against the oracle's own selection when the sets agree
+    if same:
+        ok, ov, _ = orc.gather_draft_kv(f32_to_bf16_bits(wl.draft_k), f32_to_bf16_bits(wl.draft_v),
+                                        orc.select_chunks(ref_scores[row], wl.top_k), wl.chunk_size)
+        assert (kd.view(torch.int16).cpu().numpy().view(np.uint16) == ok).all()
+
+
+# --------------------------------------------------------------------------
+# configuration 5: stress shapes with a ragged prefix
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("variant", ["wide", "chain"])
+def test_config5_stress(hx, variant):
+    wl = config_workload(5, variant=variant, sharp=(variant == "wide"))
+    res, ref_out, ref_lse, ref_scores, rel = _full_check(hx, wl, f"cfg5 {variant}")
+    assert res["scores"].shape[1] == 512
+    sel, n, _ = hx.run_select(res["scores"][0], wl.top_k)
+    check_selection(sel, ref_scores[0], wl.top_k, f"cfg5 {variant}")
+    if variant == "chain":
+        k_all = np.concatenate([wl.k_prefix, wl.k_tree], axis=1)
+        v_all = np.concatenate([wl.v_prefix, wl.v_tree], axis=1)
+        ref = orc.causal_attention_tail(wl.q, k_all, v_all)
+        assert np.abs(res["out"] - ref).max() <= TOL["bf16"] * np.abs(ref).max()
+
+
+# --------------------------------------------------------------------------
+# configuration 4 at full size, in the launch configuration the benchmark times
+# (automatic split count), all layers' worth of distinct caches sampled
+# --------------------------------------------------------------------------
+
+def test_config4_full_size_sampled(hx):
+    rng = np.random.default_rng(4242)
+    for layer in (0, 13, 31):
+        for sharp in ((False, True) if layer == 31 else (False,)):
+            wl = config_workload(4, item=layer, sharp=sharp)
+            print(f"[case] cfg4 layer {layer} sharp={sharp}", flush=True)
+            res = hx.run_verify(wl)
+            assert res["status"] == 0
+            heads = sorted(int(h) for h in rng.choice(wl.n_q_heads, size=6, replace=False))
+            G = wl.n_q_heads // wl.n_kv_heads
+            for h in heads:
+                g = h // G
+                sub = Workload(name="s", dtype=wl.dtype, n_q_heads=1, n_kv_heads=1, head_dim=wl.head_dim,
+                               prefix_len=wl.prefix_len, chunk_size=wl.chunk_size, top_k=wl.top_k,
+                               parent=wl.parent, score_row=0, needle_chunks=[], q=wl.q[:, h:h + 1],
+                               k_prefix=wl.k_prefix[g:g + 1], v_prefix=wl.v_prefix[g:g + 1],
+                               k_tree=wl.k_tree[g:g + 1], v_tree=wl.v_tree[g:g + 1])
+                ro, rl, _ = orc.verify_attention(sub.q, sub.k_prefix, sub.v_prefix, sub.k_tree, sub.v_tree, sub.parent)
+                part = {"out": res["out"][:, h:h + 1], "lse": res["lse"][h:h + 1]}
+                check_attention(sub, part, ro, rl, f"cfg4 layer {layer} head {h}")
+            if layer == 31:
+                # scores come from the last layer: all heads needed, full oracle on this one layer
+                _, _, ref_scores = oracle_all(wl)
+                check_scores(res["scores"], ref_scores, "cfg4 scores")
+                sel, n, _ = hx.run_select(res["scores"][wl.score_row], wl.top_k)
+                check_selection(sel, ref_scores[wl.score_row], wl.top_k, "cfg4 select")
+                assert set(wl.needle_chunks) <= set(int(i) for i in sel)

@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the verification hot path on one MI355X.
+
+One step = one full verification step of a Llama-3.1-8B-shaped target model at
+a 16384-token prefix: 32 layers of Hybrid Tree Attention (prefix pass + tree
+pass + merge; each layer has its own bf16 K/V cache, 2.147 GB in total, so
+every layer streams cold from HBM), then chunk scores from the last layer,
+top-32-of-512 chunk selection and the draft-KV gather.  Inputs are synthetic
+and resident in HBM before the timed region.  The whole step is captured once
+in a HIP graph and replayed, so the host launch path is not what is timed.
+
+Prints one JSON line.  `roofline` prices the dominant kernel (the prefix pass)
+by its algorithmic bytes (one layer's K+V prefix) over its average launch
+duration, measured with HIP events around a graph that holds only the 32
+prefix-pass launches.  `cpu_baseline` times the fp64 oracle on the host cores
+for a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--prefix", type=int, default=16384)
+    ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=10, help="layers the oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2505_20776_amd as sx
+    from paper_2505_20776_amd import harness
+    from workloads import config_tree
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    Hq, Hkv, d, L, B, topk = 32, 8, 128, args.prefix, 32, 32
+    parent_np = config_tree(4)
+    T = len(parent_np)
+    n_layers = args.layers
+    n_chunks = (L + B - 1) // B
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4000)
+    std = 1.0 / np.sqrt(d)
+
+    def randn(*shape):
+        return (torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+
+    q = [randn(T, Hq, d) for _ in range(n_layers)]
+    kp = [randn(Hkv, L, d) for _ in range(n_layers)]
+    vp = [randn(Hkv, L, d) for _ in range(n_layers)]
+    kt = [randn(Hkv, T, d) for _ in range(n_layers)]
+    vt = [randn(Hkv, T, d) for _ in range(n_layers)]
+    draft_k = randn(1, Hkv, L, d)
+    draft_v = randn(1, Hkv, L, d)
+    parent = torch.from_numpy(parent_np).to(dev)
+
+    plain = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
+                                 num_splits=args.num_splits)
+    last = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
+                                chunk_size=B, want_scores=True, num_splits=args.num_splits)
+    only = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
+                                num_splits=args.num_splits, flags=sx.SPECEXT_FLAG_PREFIX_ONLY)
+    outs = [torch.empty((T, Hq, d), dtype=torch.bfloat16, device=dev) for _ in range(n_layers)]
+    scores = torch.empty((n_chunks,), dtype=torch.float32, device=dev)
+    idx = torch.empty((topk,), dtype=torch.int32, device=dev)
+    n_out = torch.empty((1,), dtype=torch.int32, device=dev)
+    cap = topk * B
+    ck = torch.empty((1, Hkv, cap, d), dtype=torch.bfloat16, device=dev)
+    cv = torch.empty((1, Hkv, cap, d), dtype=torch.bfloat16, device=dev)
+    pos = torch.empty((cap,), dtype=torch.int32, device=dev)
+    length = torch.empty((1,), dtype=torch.int32, device=dev)
+
+    def step():
+        for l in range(n_layers):
+            buf = last if l == n_layers - 1 else plain
+            sx.verify_attn(buf.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, outs[l], buf.lse, buf.workspace)
+        sx.chunk_scores(last.desc, last.workspace, 0, scores)
+        sx.select_chunks(scores, n_chunks, topk, idx, n_out)
+        sx.gather_draft_kv(draft_k, draft_v, ck, cv, idx, n_out, topk, 1, Hkv, L, cap, d, B, 2, pos, length)
+
+    def prefix_only():
+        for l in range(n_layers):
+            sx.verify_attn(only.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, outs[l], only.lse, only.workspace)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(max(args.warmup, 1)):
+            step()
+        prefix_only()
+        stream.synchronize()
+        if args.no_graph:
+            run_step, run_prefix = step, prefix_only
+        else:
+            g_step = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_step, stream=stream):
+                step()
+            g_prefix = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_prefix, stream=stream):
+                prefix_only()
+            run_step, run_prefix = g_step.replay, g_prefix.replay
+            for _ in range(2):
+                run_step()
+            stream.synchronize()
+
+        # ---- timed region: exactly K steps ----
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+        # ---- dominant kernel: prefix pass, HIP events on the launch stream ----
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        run_prefix()
+        stream.synchronize()
+        e0.record(stream)
+        for _ in range(args.steps):
+            run_prefix()
+        e1.record(stream)
+        stream.synchronize()
+        prefix_us = e0.elapsed_time(e1) * 1e3 / (args.steps * n_layers)
+
+    assert int(length.item()) == cap and int(n_out.item()) == topk
+
+    bytes_per_launch = 2 * Hkv * L * d * 2                     # one layer's K and V prefix, bf16
+    flops_per_launch = 4.0 * d * T * (Hq // Hkv) * Hkv * L     # QK^T and PV, 2 flops per MAC
+    achieved_gbs = bytes_per_launch / (prefix_us * 1e-6) / 1e9
+    step_us = ms_per_step * 1e3
+    result = {
+        "metric": "us per verification step (all layers) at 16K prefix",
+        "value": round(step_us, 2),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config 4: {n_layers} layers x (Hq=32, Hkv=8, d=128) bf16, prefix {L}, 60-node tree, "
+                        f"chunk 32, top-32 of {n_chunks}, draft gather 1x8x{cap}x128",
+            "num_splits": sx.num_splits(plain.desc),
+            "graph_replay": not args.no_graph,
+            "step_hbm_GBps": round(n_layers * bytes_per_launch / (step_us * 1e-6) / 1e9, 1),
+            "step_mfma_TFLOPs": round(n_layers * flops_per_launch / (step_us * 1e-6) / 1e12, 1),
+        },
+        "roofline": {
+            "kernel": "prefix_mfma_kernel (split-K prefix pass, one layer per launch)",
+            "bound": "hbm",
+            "achieved": round(achieved_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "us_per_launch": round(prefix_us, 3),
+            "mfma_TFLOPs": round(flops_per_launch / (prefix_us * 1e-6) / 1e12, 1),
+            "mfma_frac": round(flops_per_launch / (prefix_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, n_layers, L, B, topk)
+    print(json.dumps(result))
+
+
+def cpu_baseline(args, n_layers, L, B, topk):
+    """The fp64 oracle, as it stands, on the host cores for a bounded sample."""
+    import numpy as np
+
+    import oracle as orc
+    from workloads import config_workload
+
+    sample_layers = max(1, min(args.cpu_layers, n_layers))
+    t_attn = 0.0
+    wl = None
+    for l in range(sample_layers):
+        wl = config_workload(4, item=l, prefix_len=L)
+        t0 = time.perf_counter()
+        orc.verify_attention(wl.q, wl.k_prefix, wl.v_prefix, wl.k_tree, wl.v_tree, wl.parent)
+        t_attn += time.perf_counter() - t0
+    t0 = time.perf_counter()
+    sc = orc.chunk_scores(wl.q, wl.k_prefix, wl.v_prefix, wl.k_tree, wl.v_tree, wl.parent, B)
+    sel = orc.select_chunks(sc[0], topk)
+    src = wl.k_prefix[None]
+    orc.gather_draft_kv(src, src, sel, B)
+    t_tail = time.perf_counter() - t0
+    step_s = t_attn / sample_layers * n_layers + t_tail
+    try:
+        import threadpoolctl
+        threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {
+        "value": round(step_s * 1e6, 1),
+        "unit": "us",
+        "cores": int(threads),
+        "kind": "oracle",
+        "sample": f"fp64 numpy oracle: attention of {sample_layers} of {n_layers} layers timed "
+                  f"({t_attn:.1f} s) and scaled to {n_layers}, plus chunk scores + select + gather once "
+                  f"({t_tail:.1f} s)",
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -54,6 +54,14 @@ typedef enum specext_dtype {
   SPECEXT_BF16 = 1
 } specext_dtype;
 
+/* desc->flags: run the prefix pass on the vector ALUs (fp32 FMA) even where the
+ * matrix-core kernel applies; for cross-checking the two kernels. */
+#define SPECEXT_FLAG_VALU_PREFIX 1u
+/* desc->flags: specext_verify_attn runs only the split prefix pass and stops
+ * before the tree pass and merge, so out / lse are not written.  For timing the
+ * prefix kernel on its own. */
+#define SPECEXT_FLAG_PREFIX_ONLY 2u
+
 #define SPECEXT_MAX_TREE 128           /* largest supported n_tree */
 #define SPECEXT_MAX_SPLITS 256         /* largest supported num_splits */
 
@@ -75,6 +83,8 @@ typedef struct specext_desc {
   int32_t want_scores;    /* != 0: also leave per-chunk partial sums in the workspace */
   int32_t num_splits;     /* pieces the prefix is cut into; 0 = choose automatically */
   float softmax_scale;    /* 0 = 1/sqrt(d) */
+  uint32_t flags;         /* bit set of SPECEXT_FLAG_* */
+  uint32_t reserved;      /* must be 0 */
   /* element strides; the d elements of one vector are always contiguous */
   int64_t q_stride_t, q_stride_h;       /* q[t][h][:]        default Hq*d, d  */
   int64_t kp_stride_h, kp_stride_l;     /* k_prefix[g][j][:] default L*d,  d  (v_prefix uses the same) */

@@ -18,6 +18,8 @@ SPECEXT_F32 = 0
 SPECEXT_BF16 = 1
 SPECEXT_MAX_TREE = 128
 SPECEXT_MAX_SPLITS = 256
+SPECEXT_FLAG_VALU_PREFIX = 1
+SPECEXT_FLAG_PREFIX_ONLY = 2
 
 STATUS_NAMES = {0: "SPECEXT_OK", -1: "SPECEXT_ERR_INVALID_ARG", -2: "SPECEXT_ERR_UNSUPPORTED",
                 -3: "SPECEXT_ERR_WORKSPACE_TOO_SMALL", -4: "SPECEXT_ERR_LAUNCH_FAILED"}
@@ -38,6 +40,7 @@ class specext_desc(ctypes.Structure):
         ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
         ("prefix_len", ctypes.c_int32), ("n_tree", ctypes.c_int32), ("chunk_size", ctypes.c_int32),
         ("want_scores", ctypes.c_int32), ("num_splits", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+        ("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
         ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
         ("kp_stride_h", ctypes.c_int64), ("kp_stride_l", ctypes.c_int64),
         ("kt_stride_h", ctypes.c_int64), ("kt_stride_t", ctypes.c_int64),
@@ -79,7 +82,7 @@ def load_library() -> ctypes.CDLL:
 
 def make_desc(*, dtype: int, n_q_heads: int, n_kv_heads: int, head_dim: int, prefix_len: int, n_tree: int,
               out_dtype: Optional[int] = None, chunk_size: int = 0, want_scores: bool = False,
-              num_splits: int = 0, softmax_scale: float = 0.0, **strides) -> specext_desc:
+              num_splits: int = 0, softmax_scale: float = 0.0, flags: int = 0, **strides) -> specext_desc:
     d = specext_desc()
     d.struct_size = ctypes.sizeof(specext_desc)
     d.dtype = dtype
@@ -88,6 +91,7 @@ def make_desc(*, dtype: int, n_q_heads: int, n_kv_heads: int, head_dim: int, pre
     d.prefix_len, d.n_tree = prefix_len, n_tree
     d.chunk_size, d.want_scores, d.num_splits = chunk_size, int(bool(want_scores)), num_splits
     d.softmax_scale = softmax_scale
+    d.flags = flags
     for name, val in strides.items():
         if not hasattr(d, name):
             raise TypeError(f"unknown descriptor field {name}")

@@ -46,6 +46,7 @@ int resolve(const specext_desc* d, AttnParams* p) {
   if (d->n_q_heads % d->n_kv_heads != 0) return SPECEXT_ERR_INVALID_ARG;
   if (d->want_scores && d->chunk_size <= 0) return SPECEXT_ERR_INVALID_ARG;
   if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return SPECEXT_ERR_INVALID_ARG;
+  if (d->reserved != 0 || (d->flags & ~(SPECEXT_FLAG_VALU_PREFIX | SPECEXT_FLAG_PREFIX_ONLY)) != 0) return SPECEXT_ERR_INVALID_ARG;
   if (d->dtype != SPECEXT_F32 && d->dtype != SPECEXT_BF16) return SPECEXT_ERR_UNSUPPORTED;
   if (d->out_dtype != SPECEXT_F32 && d->out_dtype != d->dtype) return SPECEXT_ERR_UNSUPPORTED;
   if (d->head_dim != 64 && d->head_dim != 128) return SPECEXT_ERR_UNSUPPORTED;
@@ -80,22 +81,33 @@ int resolve(const specext_desc* d, AttnParams* p) {
     if (s < 0 || s % 8 != 0) return SPECEXT_ERR_UNSUPPORTED;
   if (p->q_sh < p->d || p->kp_sl < p->d || p->kt_st < p->d || p->o_sh < p->d) return SPECEXT_ERR_INVALID_ARG;
 
-  // Split the prefix.  Every split but the last holds keys_per_split keys, a
-  // multiple of 64 and, with scores, of the chunk size, so that no chunk is
-  // shared by two splits.
+  // Which prefix kernel runs: the matrix-core kernel takes bf16, d = 128 and, when
+  // scores are wanted, chunk sizes that are whole 32-key tiles.
+  p->use_mfma = (p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L > 0 &&
+                 (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX))
+                    ? 1
+                    : 0;
+  p->rows_per_group = p->use_mfma ? (p->M > 32 ? 64 : 32) : 64;
+  p->score_gran = p->use_mfma ? 32 : p->B;
+  p->n_sub = p->want_scores ? (p->L + p->score_gran - 1) / p->score_gran : 0;
+
+  // Split the prefix.  Every split but the last holds keys_per_split keys: a
+  // multiple of the kernel's key granule (4 waves x 32 keys on the matrix-core
+  // path, 64 otherwise) and, with scores, of the chunk size, so that no chunk
+  // is shared by two splits.
   if (p->L == 0) {
     p->S = 0;
-    p->keys_per_split = 64;
+    p->keys_per_split = 128;
     return SPECEXT_OK;
   }
-  int64_t unit = 64;
+  int64_t unit = p->use_mfma ? 128 : 64;
   if (p->want_scores) unit = unit / gcd64(unit, p->B) * p->B;
   int want = d->num_splits;
   if (want == 0) {
-    // about two workgroups' worth of splits per compute unit across the KV heads,
-    // but at least 256 keys per split so the partials stay small next to the stream
+    // one workgroup per compute unit: splits x KV heads x row groups ~ CU count
     const int cus = device_cu_count();
-    want = (cus + p->Hkv - 1) / p->Hkv;
+    const int row_groups = (p->M + p->rows_per_group - 1) / p->rows_per_group;
+    want = cus / (p->Hkv * row_groups);
     const int by_len = static_cast<int>((p->L + 255) / 256);
     if (want > by_len) want = by_len;
     if (want < 1) want = 1;
@@ -121,7 +133,7 @@ WorkspaceLayout layout_of(const AttnParams& p) {
   w.part_o_off = off;
   off += align_up(static_cast<size_t>(p.S) * rows * p.d * sizeof(float));
   w.chunk_off = off;
-  if (p.want_scores) off += align_up(rows * static_cast<size_t>(p.C) * 2 * sizeof(float));
+  if (p.want_scores) off += align_up(rows * static_cast<size_t>(p.n_sub) * 2 * sizeof(float));
   w.total = off;
   return w;
 }
@@ -196,6 +208,7 @@ int specext_verify_attn(const specext_desc* desc, const void* q, const void* k_p
     const hipError_t e = prefix_mfma_supports(p) ? launch_prefix_mfma(p, s) : launch_prefix_generic(p, s);
     if (e != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
   }
+  if (desc->flags & SPECEXT_FLAG_PREFIX_ONLY) return SPECEXT_OK;
   if (launch_tree_merge(p, s) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
   return SPECEXT_OK;
 }

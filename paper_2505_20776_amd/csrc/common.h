@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "specext.h"
 
 namespace specext {
@@ -31,9 +33,11 @@ struct AttnParams {
   float* lse2;         // [Hq*T] base-2 log-sum-exp per rid
   float* part_ml;      // [S][Hq*T][2]  (running max, running sum) per split
   float* part_o;       // [S][Hq*T][d]  unnormalised partial outputs
-  float* chunk_part;   // [Hq*T][C][2]  (sum of exp2(s - ref), ref) per chunk; null unless want_scores
+  float* chunk_part;   // [Hkv][n_sub][M][2]  (sum of exp2(s - ref), ref) per score block; null unless want_scores
   int32_t Hq, Hkv, G, d, L, T, M;
   int32_t B, C, S, keys_per_split, want_scores;
+  int32_t score_gran, n_sub;      // keys per score block (32 on the MFMA path, else B) and their count
+  int32_t use_mfma, rows_per_group;
   int32_t in_dtype, out_dtype;
   float scale_log2;
   int64_t q_st, q_sh, kp_sh, kp_sl, kt_sh, kt_st, o_st, o_sh;

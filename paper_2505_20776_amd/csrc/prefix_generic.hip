@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void prefix_generic_kernel(AttnParam
         const int j = base + r;
         if ((j + 1) % p.B == 0 || j + 1 == key_hi) {   // chunk closes (splits start on chunk boundaries)
           if (row_ok) {
-            float* cp = p.chunk_part + (static_cast<int64_t>(rid) * p.C + j / p.B) * 2;
+            float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + j / p.B) * p.M + m) * 2;
             cp[0] = chunk_sum;
             cp[1] = new_max;
           }

@@ -12,19 +12,27 @@ namespace {
 // chunk scores
 // --------------------------------------------------------------------------
 
-// scores[r][c] = (1/Hq) * sum_h  sum_c(h, t) * exp2(ref - lse2(h, t)) / |c|
-// with heads added in ascending order (fixed-order fp32 sum).
+// scores[r][c] = (1/Hq) * sum_h  sum_blocks  blocksum(h, t) * exp2(ref - lse2(h, t)) / |c|
+// The prefix pass leaves one (sum, ref) pair per score block (score_gran keys;
+// a chunk is a whole number of blocks).  Heads and blocks are added in
+// ascending order: a fixed-order fp32 sum.
 __global__ __launch_bounds__(256) void chunk_scores_kernel(AttnParams p, int first_row, float* scores) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   const int t = first_row + blockIdx.y;
   if (c >= p.C) return;
   const int size = min(p.B, p.L - c * p.B);
+  const int per_chunk = p.B / p.score_gran;
+  const int sub_lo = c * per_chunk;
+  const int sub_hi = min(sub_lo + per_chunk, p.n_sub);
   float acc = 0.f;
   for (int h = 0; h < p.Hq; ++h) {
     const int g = h / p.G;
-    const int rid = g * p.M + t * p.G + (h - g * p.G);
-    const float* cp = p.chunk_part + (static_cast<int64_t>(rid) * p.C + c) * 2;
-    acc += cp[0] * exp2f(cp[1] - p.lse2[rid]);
+    const int m = t * p.G + (h - g * p.G);
+    const float l2 = p.lse2[g * p.M + m];
+    for (int sb = sub_lo; sb < sub_hi; ++sb) {
+      const float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sb) * p.M + m) * 2;
+      acc += cp[0] * exp2f(cp[1] - l2);
+    }
   }
   scores[static_cast<int64_t>(blockIdx.y) * p.C + c] = acc / (static_cast<float>(size) * static_cast<float>(p.Hq));
 }

@@ -33,12 +33,12 @@ class VerifyBuffers:
 
 def make_buffers(*, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, prefix_len: int, n_tree: int,
                  chunk_size: int = 0, want_scores: bool = False, num_splits: int = 0, out_dtype: Optional[str] = None,
-                 softmax_scale: float = 0.0, device="cuda") -> VerifyBuffers:
+                 softmax_scale: float = 0.0, flags: int = 0, device="cuda") -> VerifyBuffers:
     odt = out_dtype or dtype
     desc = sx.make_desc(dtype=dtype_code(dtype), out_dtype=dtype_code(odt), n_q_heads=n_q_heads,
                         n_kv_heads=n_kv_heads, head_dim=head_dim, prefix_len=prefix_len, n_tree=n_tree,
                         chunk_size=chunk_size, want_scores=want_scores, num_splits=num_splits,
-                        softmax_scale=softmax_scale)
+                        softmax_scale=softmax_scale, flags=flags)
     nbytes = sx.workspace_bytes(desc)
     if nbytes == 0:
         raise ValueError("descriptor rejected by specext_workspace_bytes")
@@ -53,7 +53,8 @@ def make_buffers(*, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, 
     return VerifyBuffers(desc, out, lse, ws, scores)
 
 
-def run_verify(wl, *, num_splits: int = 0, want_scores: bool = True, out_dtype: Optional[str] = None):
+def run_verify(wl, *, num_splits: int = 0, want_scores: bool = True, out_dtype: Optional[str] = None,
+               flags: int = 0):
     """Run verify_attn (+ chunk_scores for every row) on a workloads.Workload.
     Returns dict of numpy arrays: out fp32 [T,Hq,d], lse [Hq,T], scores [T,C] or None, status int."""
     dev = "cuda"
@@ -66,7 +67,8 @@ def run_verify(wl, *, num_splits: int = 0, want_scores: bool = True, out_dtype: 
     want_scores = want_scores and wl.prefix_len > 0
     buf = make_buffers(dtype=wl.dtype, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
                        prefix_len=wl.prefix_len, n_tree=wl.n_tree, chunk_size=wl.chunk_size,
-                       want_scores=want_scores, num_splits=num_splits, out_dtype=out_dtype, device=dev)
+                       want_scores=want_scores, num_splits=num_splits, out_dtype=out_dtype, flags=flags,
+                       device=dev)
     sx.verify_attn(buf.desc, q, kp if wl.prefix_len else None, vp if wl.prefix_len else None, kt, vt, parent,
                    buf.out, buf.lse, buf.workspace)
     if want_scores:

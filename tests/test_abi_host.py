@@ -34,9 +34,9 @@ def test_every_declared_symbol_is_exported(sx):
 
 
 def test_descriptor_layout_matches_header(sx):
-    # 12 four-byte fields then 8 eight-byte strides, naturally aligned
-    assert ctypes.sizeof(sx.specext_desc) == 12 * 4 + 8 * 8
-    assert sx.specext_desc.q_stride_t.offset == 48
+    # 14 four-byte fields then 8 eight-byte strides, naturally aligned
+    assert ctypes.sizeof(sx.specext_desc) == 14 * 4 + 8 * 8
+    assert sx.specext_desc.q_stride_t.offset == 56
 
 
 def _good(sx, **kw):
@@ -59,14 +59,16 @@ def test_workspace_and_splits(sx):
     d = _good(sx, prefix_len=0)
     assert sx.num_splits(d) == 0 and sx.workspace_bytes(d) > 0
     d = _good(sx, prefix_len=100, num_splits=200)
-    assert sx.num_splits(d) == 2                        # 64-key granularity
+    assert sx.num_splits(d) == 1                        # matrix-core kernel: 128-key granule
+    d = _good(sx, prefix_len=100, num_splits=200, flags=sx.SPECEXT_FLAG_VALU_PREFIX)
+    assert sx.num_splits(d) == 2                        # vector-ALU kernel: 64-key granule
 
 
 @pytest.mark.parametrize("field,value,status", [
     ("struct_size", 4, -1), ("n_q_heads", 0, -1), ("n_kv_heads", 5, -1), ("prefix_len", -1, -1),
     ("n_tree", 0, -1), ("chunk_size", 0, -1), ("num_splits", -2, -1), ("softmax_scale", -1.0, -1),
     ("dtype", 7, -2), ("head_dim", 96, -2), ("n_tree", 129, -2), ("num_splits", 257, -2),
-    ("q_stride_h", 12, -2), ("kp_stride_l", 64, -1),
+    ("q_stride_h", 12, -2), ("kp_stride_l", 64, -1), ("reserved", 1, -1), ("flags", 4, -1),
 ])
 def test_bad_descriptor_is_rejected(sx, field, value, status):
     d = _good(sx)

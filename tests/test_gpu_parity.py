@@ -361,3 +361,21 @@ def test_config4_full_size_sampled(hx):
                 sel, n, _ = hx.run_select(res["scores"][wl.score_row], wl.top_k)
                 check_selection(sel, ref_scores[wl.score_row], wl.top_k, "cfg4 select")
                 assert set(wl.needle_chunks) <= set(int(i) for i in sel)
+
+
+# --------------------------------------------------------------------------
+# the vector-ALU prefix kernel on bf16 inputs (the matrix-core kernel's fallback
+# for other head sizes / chunk sizes) against the oracle, and the two kernels
+# against each other
+# --------------------------------------------------------------------------
+
+def test_valu_prefix_kernel_on_bf16(hx):
+    import paper_2505_20776_amd as sx
+    wl = config_workload(2, sharp=True, prefix_len=2048 - 37)
+    ref_out, ref_lse, ref_scores = oracle_all(wl)
+    a = hx.run_verify(wl, flags=sx.SPECEXT_FLAG_VALU_PREFIX)
+    check_attention(wl, a, ref_out, ref_lse, "valu kernel")
+    check_scores(a["scores"], ref_scores, "valu kernel")
+    b = hx.run_verify(wl)
+    assert np.abs(a["out"] - b["out"]).max() <= 2e-2 * np.abs(ref_out).max()
+    assert np.abs(a["scores"] - b["scores"]).max() <= 1e-4 * ref_scores.max()

@@ -83,7 +83,7 @@ int resolve(const specext_desc* d, AttnParams* p) {
 
   // Which prefix kernel runs: the matrix-core kernel takes bf16, d = 128 and, when
   // scores are wanted, chunk sizes that are whole 32-key tiles.
-  p->use_mfma = (p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L > 0 &&
+  p->use_mfma = (p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L >= 32 &&
                  (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX))
                     ? 1
                     : 0;

@@ -39,12 +39,20 @@ typedef __attribute__((ext_vector_type(4))) uint32_t uintx4;
 constexpr int kWaves = 4;
 constexpr int kTile = 32;                         // keys per wave tile
 constexpr int kD = 128;                           // head_dim this kernel is written for
-constexpr int kRowBytes = kD * 2;                 // one bf16 K or V row
-constexpr int kStageBytes = 2 * kTile * kRowBytes;  // K tile + V tile of one wave
+constexpr int kRowBytes = kD * 2;                 // one bf16 K or V row in LDS
+constexpr int kTileBytes = kTile * kRowBytes;     // 8 KB: one K (or V) tile
+constexpr int kBufBytes = 2 * kTileBytes;         // K tile + V tile
+constexpr int kStageBytes = 2 * kBufBytes;        // double buffer of one wave
 constexpr int kMergeFloatsPerWave = 4 * 2 * 16 * 64;   // O^T dump at RB = 2
-constexpr int kLdsBytes = kWaves * kMergeFloatsPerWave * 4 + kWaves * 2 * 2 * 32 * 4;
+constexpr int kMergeBytes = kWaves * kMergeFloatsPerWave * 4 + kWaves * 2 * 2 * 32 * 4;
+constexpr int kLdsBytes = kMergeBytes > kWaves * kStageBytes ? kMergeBytes : kWaves * kStageBytes;
+// The running reference of a row only moves when a tile's max exceeds it by more
+// than this many powers of two, so exp2(s - ref) stays below 2^kLazyLog2.
+constexpr float kLazyLog2 = 10.f;
 
 typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -65,12 +73,10 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c32 = lane & 31;
   const int hf = lane >> 5;
 
-  // blockIdx.x enumerates (row group, split, head) with the row group slowest, so
-  // that ids of one (split, head) differ by a multiple of S * Hkv.
   const int split = blockIdx.x;
   const int g = blockIdx.y;
   const int row0 = blockIdx.z * (32 * RB);
@@ -79,8 +85,9 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
   const int key_hi = min(p.L, key_lo + p.keys_per_split);
   const int n_tiles = (key_hi - key_lo + kTile - 1) / kTile;
 
-  const uint16_t* __restrict__ kbase = static_cast<const uint16_t*>(p.kp) + static_cast<int64_t>(g) * p.kp_sh;
-  const uint16_t* __restrict__ vbase = static_cast<const uint16_t*>(p.vp) + static_cast<int64_t>(g) * p.kp_sh;
+  const int64_t row_bytes = p.kp_sl * 2;
+  const unsigned char* kbase = static_cast<const unsigned char*>(p.kp) + static_cast<int64_t>(g) * p.kp_sh * 2;
+  const unsigned char* vbase = static_cast<const unsigned char*>(p.vp) + static_cast<int64_t>(g) * p.kp_sh * 2;
 
   // ---- Q fragments (B operand of S^T): lane = row c32, 8 consecutive d per k-step ----
   bf16x8 qf[RB][8];
@@ -99,23 +106,35 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
     }
   }
 
-  // ---- per-wave LDS staging: K tile then V tile, 32 rows x 256 B each, 16-byte
-  // chunks XOR-swizzled so that the operand reads below are bank-conflict free ----
-  unsigned char* kst = lds + wave * kStageBytes;
-  unsigned char* vst = kst + kTile * kRowBytes;
+  // All query loads have landed before the main loop starts; said through the builtin
+  // so that the compiler's own wait bookkeeping sees it and adds no vmcnt wait of its
+  // own inside the loop (0x0F70 = vmcnt(0), other counters untouched).
+  __builtin_amdgcn_s_waitcnt(0x0F70);
 
-  // global -> LDS mapping of one tile: 8 steps, step `it` covers keys 4*it .. 4*it+3
-  const int ld_key = lane >> 4;        // + 4 * it
-  const int ld_ch = lane & 15;
+  // ---- per-wave LDS staging, double buffered: [buffer][K tile | V tile], each tile
+  // 32 rows x 256 B.  The tiles are filled by direct global->LDS loads: one load
+  // instruction writes 1 KB = 4 consecutive rows, lane i landing at byte 16*i.  The
+  // 16-byte chunks of a row are XOR-swizzled (K: chunk ^ (row & 15), V: chunk ^
+  // ((row & 3) << 2)) so that the operand reads are bank-conflict free; since the
+  // LDS side of the load is fixed, the swizzle is applied to the global address.
+  unsigned char* stage = lds + wave * kStageBytes;
+  const int ld_row = lane >> 4;          // row within the 4-row block of one load
+  const int ld_slot = lane & 15;         // LDS chunk slot this lane fills
+  unsigned k_voff[4];                    // per-lane global byte offset of K loads, by (it & 3)
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    k_voff[i] = static_cast<unsigned>(ld_row * row_bytes) + ((ld_slot ^ ((4 * i + ld_row) & 15)) << 4);
+  const unsigned v_voff = static_cast<unsigned>(ld_row * row_bytes) + ((ld_slot ^ (ld_row << 2)) << 4);
+
   // K operand read: row c32, chunk (2*ks + hf) ^ (c32 & 15)
   const int k_rd_base = c32 * kRowBytes + ((hf ^ (c32 & 1)) << 4);
   const int k_rd_xor = c32 & 14;
-  // V transpose read: group of 16 lanes reads 4 keys x 16 dcols
+  // V transpose read: a group of 16 lanes reads 4 keys x 16 dcols
   const int li = lane & 15;
   const int grp_col = (lane >> 4) & 1;                  // which 16-column half of the 32-dcol block
   const int v_key_in = 4 * hf + (li >> 2);              // + 16 * j (+ 8)
-  const int v_rd_base = v_key_in * kRowBytes + ((2 * grp_col + ((li & 3) >> 1)) << 4) + ((li & 1) << 3);
-  const int v_q4 = li >> 2;                             // (key & 3) of the row this lane addresses
+  const int v_rd_base = kTileBytes + v_key_in * kRowBytes + ((2 * grp_col + ((li & 3) >> 1)) << 4) + ((li & 1) << 3);
+  const int v_q4 = li >> 2;                             // (row & 3) of the row this lane addresses
 
   floatx16 acc_o[4][RB];
 #pragma unroll
@@ -124,42 +143,54 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc_o[db][rb][r] = 0.f;
-  float run_max[RB], run_sum[RB];                       // raw-logit max; lane-partial sum
+  float ref[RB], run_sum[RB];        // reference logit (raw units) the exponentials are taken against; lane-partial sum
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    run_max[rb] = -INFINITY;
+    ref[rb] = -INFINITY;
     run_sum[rb] = 0.f;
   }
   const float c = p.scale_log2;
+  const float lazy_raw = kLazyLog2 / c;      // the threshold in raw-logit units
 
-  uintx4 stage_k[8], stage_v[8];
-  auto issue_loads = [&](int tile) {
-    const int key0 = key_lo + tile * kTile;
+  // first key of the 32 rows a tile loads: the last tile of a ragged split is shifted
+  // back so that it ends exactly at key_hi (no load ever leaves the prefix); its rows
+  // below the tile's own first key were already handled by another tile and are masked
+  auto tile_first_row = [&](int tile) { return min(key_lo + tile * kTile, key_hi - kTile); };
+
+  // The loads are issued through inline assembly on purpose: the compiler then does
+  // not know that they write LDS and leaves the waiting to the explicit s_waitcnt
+  // below, instead of draining the whole load queue (and with it the prefetch of the
+  // next tile) before the first LDS read of every tile.
+  const unsigned stage_lds = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)stage));
+  auto issue_loads = [&](int tile, int buf) {
+    const int64_t tile_off = static_cast<int64_t>(tile_first_row(tile)) * row_bytes;
+    const unsigned char* kt = kbase + tile_off;
+    const unsigned char* vt = vbase + tile_off;
+    const unsigned dst = stage_lds + buf * kBufBytes;
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
-      const int j = min(key0 + 4 * it + ld_key, p.L - 1);    // rows past the end repeat the last key
-      const int64_t off = static_cast<int64_t>(j) * p.kp_sl + ld_ch * 8;
-      stage_k[it] = *reinterpret_cast<const uintx4*>(kbase + off);
-      stage_v[it] = *reinterpret_cast<const uintx4*>(vbase + off);
+      const unsigned char* kr = kt + it * 4 * row_bytes;
+      const unsigned char* vr = vt + it * 4 * row_bytes;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(dst + it * 1024), "v"(k_voff[it & 3]), "s"(kr) : "memory", "m0");
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(dst + kTileBytes + it * 1024), "v"(v_voff), "s"(vr) : "memory", "m0");
     }
   };
 
   int tile = wave;
-  if (tile < n_tiles) issue_loads(tile);
+  int buf = 0;
+  if (tile < n_tiles) issue_loads(tile, 0);
 
-  for (; tile < n_tiles; tile += kWaves) {
-    // registers -> LDS (swizzled)
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int key = 4 * it + ld_key;
-      *reinterpret_cast<uintx4*>(kst + key * kRowBytes + ((ld_ch ^ (key & 15)) << 4)) = stage_k[it];
-      *reinterpret_cast<uintx4*>(vst + key * kRowBytes + ((ld_ch ^ ((key & 3) << 2)) << 4)) = stage_v[it];
-    }
+  for (; tile < n_tiles; tile += kWaves, buf ^= 1) {
     const int next = tile + kWaves;
-    if (next < n_tiles) issue_loads(next);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (next < n_tiles) {
+      issue_loads(next, buf ^ 1);
+      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");     // everything older than the 16 loads just issued
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    const unsigned char* kst = stage + buf * kBufBytes;
 
     // ---- S^T = K Q^T ----
     floatx16 acc_s[RB];
@@ -176,37 +207,38 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
         acc_s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc_s[rb], 0, 0, 0);
     }
 
-    // ---- mask keys past the end of the split (last tile only) ----
+    // ---- rows of a shifted last tile that belong to an earlier tile ----
     const int key0 = key_lo + tile * kTile;
-    if (key0 + kTile > key_hi) {
+    const int first_row = tile_first_row(tile);
+    if (first_row < key0) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int key = key0 + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (key >= key_hi) {
+        const int key = first_row + 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (key < key0) {
 #pragma unroll
           for (int rb = 0; rb < RB; ++rb) acc_s[rb][r] = -INFINITY;
         }
       }
     }
 
-    // ---- online softmax, one query row per lane pair ----
-    float tile_max[RB];
+    // ---- online softmax, one query row per lane pair; the reference moves lazily ----
     bool grow = false;
+    float tile_max[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       float mx = acc_s[rb][0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc_s[rb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       tile_max[rb] = mx;
-      grow |= mx > run_max[rb];
+      grow |= mx > ref[rb] + lazy_raw;
     }
-    if (__any(grow)) {     // the running max moved for some row of this wave: rescale (rare in steady state)
+    if (__any(grow)) {     // some row of this wave outgrew its reference: move every reference up
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
-        const float new_max = fmaxf(run_max[rb], tile_max[rb]);
-        const float alpha = fast_exp2((run_max[rb] - new_max) * c);     // 0 on the first tile
-        run_max[rb] = new_max;
+        const float mx = fmaxf(tile_max[rb], __shfl_xor(tile_max[rb], 32, 64));
+        const float new_ref = fmaxf(ref[rb], mx);
+        const float alpha = fast_exp2((ref[rb] - new_ref) * c);     // 0 on the first tile
+        ref[rb] = new_ref;
         run_sum[rb] *= alpha;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -217,7 +249,7 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
     bf16x8 pf[RB][2];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      const float mc = run_max[rb] * c;
+      const float mc = ref[rb] * c;
       float part = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -245,9 +277,9 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_shortx4*)(vst + col_off + (16 * j) * kRowBytes));
+            (lds_shortx4*)(kst + col_off + (16 * j) * kRowBytes));
         const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_shortx4*)(vst + col_off + (16 * j + 8) * kRowBytes));
+            (lds_shortx4*)(kst + col_off + (16 * j + 8) * kRowBytes));
         const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
@@ -255,12 +287,14 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
           acc_o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb][j], acc_o[db][rb], 0, 0, 0);
       }
     }
-    __builtin_amdgcn_wave_barrier();
   }
 
   // ---- merge the four waves' partials through LDS; wave w finishes dcols 32w..32w+31 ----
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) run_sum[rb] += __shfl_xor(run_sum[rb], 32, 64);
+  for (int rb = 0; rb < RB; ++rb) {
+    run_sum[rb] += __shfl_xor(run_sum[rb], 32, 64);
+    ref[rb] = fmaxf(ref[rb], __shfl_xor(ref[rb], 32, 64));      // both lanes of a pair hold the same value already
+  }
   __syncthreads();                                  // every wave is done with its staging area
   float* dump = reinterpret_cast<float*>(lds);
   float* ml = dump + kWaves * kMergeFloatsPerWave;  // [wave][rb][2][32]
@@ -274,7 +308,7 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
   if (hf == 0) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      ml[((wave * 2 + rb) * 2 + 0) * 32 + c32] = run_max[rb] * c;
+      ml[((wave * 2 + rb) * 2 + 0) * 32 + c32] = ref[rb] * c;
       ml[((wave * 2 + rb) * 2 + 1) * 32 + c32] = run_sum[rb];
     }
   }

@@ -41,8 +41,9 @@ constexpr int kTile = 32;                         // keys per wave tile
 constexpr int kD = 128;                           // head_dim this kernel is written for
 constexpr int kRowBytes = kD * 2;                 // one bf16 K or V row in LDS
 constexpr int kTileBytes = kTile * kRowBytes;     // 8 KB: one K (or V) tile
-constexpr int kBufBytes = 2 * kTileBytes;         // K tile + V tile
-constexpr int kStageBytes = 2 * kBufBytes;        // double buffer of one wave
+constexpr int kKSlots = 3;                        // ring of K tiles per wave
+constexpr int kVSlots = 2;                        // ring of V tiles per wave
+constexpr int kStageBytes = (kKSlots + kVSlots) * kTileBytes;   // 40 KB per wave, 160 KB per workgroup
 constexpr int kMergeFloatsPerWave = 4 * 2 * 16 * 64;   // O^T dump at RB = 2
 constexpr int kMergeBytes = kWaves * kMergeFloatsPerWave * 4 + kWaves * 2 * 2 * 32 * 4;
 constexpr int kLdsBytes = kMergeBytes > kWaves * kStageBytes ? kMergeBytes : kWaves * kStageBytes;
@@ -52,7 +53,6 @@ constexpr float kLazyLog2 = 10.f;
 
 typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
 typedef __attribute__((address_space(3))) void lds_void;
-typedef const __attribute__((address_space(1))) void global_void;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -66,6 +66,18 @@ __device__ __forceinline__ bf16x8 pack8(const floatx16& v, int first) {
     out[e + 1] = b[1];
   }
   return out;
+}
+
+// Wait until at most 8 * groups vector-memory operations are outstanding.
+__device__ __forceinline__ void wait_vm_groups(int groups) {
+  switch (groups) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 1: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+    case 2: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+    case 3: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+    case 4: asm volatile("s_waitcnt vmcnt(32)" ::: "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(40)" ::: "memory"); break;
+  }
 }
 
 template <int RB, bool SCORES>
@@ -84,6 +96,8 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
   const int key_lo = split * p.keys_per_split;
   const int key_hi = min(p.L, key_lo + p.keys_per_split);
   const int n_tiles = (key_hi - key_lo + kTile - 1) / kTile;
+  // this wave takes tiles wave, wave + 4, ...: n of them, numbered j = 0 .. n-1
+  const int n = (n_tiles - wave + kWaves - 1) / kWaves;
 
   const int64_t row_bytes = p.kp_sl * 2;
   const unsigned char* kbase = static_cast<const unsigned char*>(p.kp) + static_cast<int64_t>(g) * p.kp_sh * 2;
@@ -105,19 +119,19 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
       qf[rb][ks] = __builtin_bit_cast(bf16x8, w);
     }
   }
-
   // All query loads have landed before the main loop starts; said through the builtin
   // so that the compiler's own wait bookkeeping sees it and adds no vmcnt wait of its
   // own inside the loop (0x0F70 = vmcnt(0), other counters untouched).
   __builtin_amdgcn_s_waitcnt(0x0F70);
 
-  // ---- per-wave LDS staging, double buffered: [buffer][K tile | V tile], each tile
-  // 32 rows x 256 B.  The tiles are filled by direct global->LDS loads: one load
-  // instruction writes 1 KB = 4 consecutive rows, lane i landing at byte 16*i.  The
-  // 16-byte chunks of a row are XOR-swizzled (K: chunk ^ (row & 15), V: chunk ^
+  // ---- per-wave LDS staging: a ring of 3 K tiles and a ring of 2 V tiles, each
+  // tile 32 rows x 256 B, filled by direct global->LDS loads: one load instruction
+  // writes 1 KB = 4 consecutive rows, lane i landing at byte 16*i.  The 16-byte
+  // chunks of a row are XOR-swizzled (K: chunk ^ (row & 15), V: chunk ^
   // ((row & 3) << 2)) so that the operand reads are bank-conflict free; since the
-  // LDS side of the load is fixed, the swizzle is applied to the global address.
+  // LDS side of such a load is fixed, the swizzle is applied to the global address.
   unsigned char* stage = lds + wave * kStageBytes;
+  const unsigned stage_lds = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)stage));
   const int ld_row = lane >> 4;          // row within the 4-row block of one load
   const int ld_slot = lane & 15;         // LDS chunk slot this lane fills
   unsigned k_voff[4];                    // per-lane global byte offset of K loads, by (it & 3)
@@ -133,7 +147,7 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
   const int li = lane & 15;
   const int grp_col = (lane >> 4) & 1;                  // which 16-column half of the 32-dcol block
   const int v_key_in = 4 * hf + (li >> 2);              // + 16 * j (+ 8)
-  const int v_rd_base = kTileBytes + v_key_in * kRowBytes + ((2 * grp_col + ((li & 3) >> 1)) << 4) + ((li & 1) << 3);
+  const int v_rd_base = v_key_in * kRowBytes + ((2 * grp_col + ((li & 3) >> 1)) << 4) + ((li & 1) << 3);
   const int v_q4 = li >> 2;                             // (row & 3) of the row this lane addresses
 
   floatx16 acc_o[4][RB];
@@ -152,87 +166,87 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
   const float c = p.scale_log2;
   const float lazy_raw = kLazyLog2 / c;      // the threshold in raw-logit units
 
-  // first key of the 32 rows a tile loads: the last tile of a ragged split is shifted
+  // First key of the 32 rows tile j loads.  The last tile of a ragged split is shifted
   // back so that it ends exactly at key_hi (no load ever leaves the prefix); its rows
-  // below the tile's own first key were already handled by another tile and are masked
-  auto tile_first_row = [&](int tile) { return min(key_lo + tile * kTile, key_hi - kTile); };
+  // below the tile's own first key were already handled by another tile and are masked.
+  auto tile_key0 = [&](int j) { return key_lo + (wave + kWaves * j) * kTile; };
+  auto tile_first_row = [&](int j) { return min(tile_key0(j), key_hi - kTile); };
 
   // The loads are issued through inline assembly on purpose: the compiler then does
-  // not know that they write LDS and leaves the waiting to the explicit s_waitcnt
-  // below, instead of draining the whole load queue (and with it the prefetch of the
-  // next tile) before the first LDS read of every tile.
-  const unsigned stage_lds = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)stage));
-  auto issue_loads = [&](int tile, int buf) {
-    const int64_t tile_off = static_cast<int64_t>(tile_first_row(tile)) * row_bytes;
-    const unsigned char* kt = kbase + tile_off;
-    const unsigned char* vt = vbase + tile_off;
-    const unsigned dst = stage_lds + buf * kBufBytes;
+  // not know that they write LDS and leaves the waiting to the explicit s_waitcnt,
+  // instead of draining the whole load queue (and with it the prefetch of later
+  // tiles) before the first LDS read of every tile.
+  auto issue_tile = [&](const unsigned char* base, int j, unsigned dst, bool is_k) {
+    const unsigned char* src = base + static_cast<int64_t>(tile_first_row(j)) * row_bytes;
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
-      const unsigned char* kr = kt + it * 4 * row_bytes;
-      const unsigned char* vr = vt + it * 4 * row_bytes;
+      const unsigned char* r = src + it * 4 * row_bytes;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(dst + it * 1024), "v"(k_voff[it & 3]), "s"(kr) : "memory", "m0");
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :: "s"(dst + kTileBytes + it * 1024), "v"(v_voff), "s"(vr) : "memory", "m0");
+                   :: "s"(dst + it * 1024), "v"(is_k ? k_voff[it & 3] : v_voff), "s"(r) : "memory", "m0");
+    }
+  };
+  auto issue_k = [&](int j) { issue_tile(kbase, j, stage_lds + (j % kKSlots) * kTileBytes, true); };
+  auto issue_v = [&](int j) { issue_tile(vbase, j, stage_lds + (kKSlots + j % kVSlots) * kTileBytes, false); };
+
+  bf16x8 kf[8];
+  auto read_k = [&](int j) {
+    const unsigned char* kst = stage + (j % kKSlots) * kTileBytes + k_rd_base;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uintx4 kw = *reinterpret_cast<const uintx4*>(kst + (((2 * ks) ^ k_rd_xor) << 4));
+      kf[ks] = __builtin_bit_cast(bf16x8, kw);
+    }
+  };
+  bf16x8 vf[4][2];
+  auto read_v = [&](int j) {
+    const unsigned char* vst = stage + (kKSlots + j % kVSlots) * kTileBytes + v_rd_base;
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      const unsigned char* col = vst + ((db ^ v_q4) << 6);
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(col + (16 * jj) * kRowBytes));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(col + (16 * jj + 8) * kRowBytes));
+        const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        vf[db][jj] = __builtin_bit_cast(bf16x8, both);
+      }
     }
   };
 
-  int tile = wave;
-  int buf = 0;
-  if (tile < n_tiles) issue_loads(tile, 0);
+  floatx16 s_v[RB];        // logits of the tile whose softmax comes next
+  float tile_max[RB];
+  bf16x8 pf[RB][2];
 
-  for (; tile < n_tiles; tile += kWaves, buf ^= 1) {
-    const int next = tile + kWaves;
-    if (next < n_tiles) {
-      issue_loads(next, buf ^ 1);
-      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");     // everything older than the 16 loads just issued
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    const unsigned char* kst = stage + buf * kBufBytes;
-
-    // ---- S^T = K Q^T ----
-    floatx16 acc_s[RB];
+  // mask the rows of a shifted last tile that belong to an earlier tile, then the lane-local row max
+  auto mask_and_max = [&](int j, bool may_be_shifted) {
+    if (may_be_shifted) {
+      const int key0 = tile_key0(j);
+      const int first_row = tile_first_row(j);
+      if (first_row < key0) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+        for (int r = 0; r < 16; ++r) {
+          const int key = first_row + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (key < key0) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc_s[rb][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const uintx4 kw = *reinterpret_cast<const uintx4*>(kst + k_rd_base + (((2 * ks) ^ k_rd_xor) << 4));
-      const bf16x8 kf = __builtin_bit_cast(bf16x8, kw);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        acc_s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc_s[rb], 0, 0, 0);
-    }
-
-    // ---- rows of a shifted last tile that belong to an earlier tile ----
-    const int key0 = key_lo + tile * kTile;
-    const int first_row = tile_first_row(tile);
-    if (first_row < key0) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = first_row + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (key < key0) {
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb) acc_s[rb][r] = -INFINITY;
+            for (int rb = 0; rb < RB; ++rb) s_v[rb][r] = -INFINITY;
+          }
         }
       }
     }
-
-    // ---- online softmax, one query row per lane pair; the reference moves lazily ----
-    bool grow = false;
-    float tile_max[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float mx = acc_s[rb][0];
+      float mx = fmaxf(s_v[rb][0], s_v[rb][1]);
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc_s[rb][r]);
+      for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s_v[rb][r], s_v[rb][r + 1]));
       tile_max[rb] = mx;
-      grow |= mx > ref[rb] + lazy_raw;
     }
-    if (__any(grow)) {     // some row of this wave outgrew its reference: move every reference up
+  };
+  // move the references up if some row of this wave outgrew its own by the lazy margin
+  auto lazy_rescale = [&]() {
+    bool grow = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) grow |= tile_max[rb] > ref[rb] + lazy_raw;
+    if (__any(grow)) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         const float mx = fmaxf(tile_max[rb], __shfl_xor(tile_max[rb], 32, 64));
@@ -246,15 +260,17 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
           for (int r = 0; r < 16; ++r) acc_o[db][rb][r] *= alpha;
       }
     }
-    bf16x8 pf[RB][2];
+  };
+  // exponentials of s_v against the references -> P^T fragments, row sums, score blocks
+  auto exp_and_pack = [&](int j) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       const float mc = ref[rb] * c;
       float part = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float pr = fast_exp2(fmaf(acc_s[rb][r], c, -mc));
-        acc_s[rb][r] = pr;
+        const float pr = fast_exp2(fmaf(s_v[rb][r], c, -mc));
+        s_v[rb][r] = pr;
         part += pr;
       }
       run_sum[rb] += part;
@@ -262,29 +278,113 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_mfma_kernel(AttnParams p) 
         const float tot = part + __shfl_xor(part, 32, 64);
         const int m = row0 + 32 * rb + c32;
         if (hf == 0 && m < p.M) {
-          float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + key0 / kTile) * p.M + m) * 2;
+          float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + tile_key0(j) / kTile) * p.M + m) * 2;
           *reinterpret_cast<floatx2*>(cp) = floatx2{tot, mc};
         }
       }
-      pf[rb][0] = pack8(acc_s[rb], 0);
-      pf[rb][1] = pack8(acc_s[rb], 8);
+      pf[rb][0] = pack8(s_v[rb], 0);
+      pf[rb][1] = pack8(s_v[rb], 8);
     }
-
-    // ---- O^T += V^T P^T ----
+  };
+  // S^T = K Q^T for the tile whose K fragments are in kf
+  auto qk = [&](floatx16 (&acc_s)[RB]) {
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      const int col_off = v_rd_base + ((db ^ v_q4) << 6);
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_shortx4*)(kst + col_off + (16 * j) * kRowBytes));
-        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_shortx4*)(kst + col_off + (16 * j + 8) * kRowBytes));
-        const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+      for (int r = 0; r < 16; ++r) acc_s[rb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        acc_s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], acc_s[rb], 0, 0, 0);
+  };
+  auto pv = [&]() {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-          acc_o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[rb][j], acc_o[db][rb], 0, 0, 0);
+          acc_o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][jj], pf[rb][jj], acc_o[db][rb], 0, 0, 0);
+  };
+
+  if (n > 0) {
+    // prologue: fill the rings (K0 V0 K1 V1 K2, and K3 once K0 has left its slot), logits of tile 0
+    issue_k(0);
+    issue_v(0);
+    if (n > 1) {
+      issue_k(1);
+      issue_v(1);
+    }
+    if (n > 2) issue_k(2);
+    wait_vm_groups(1 + (n > 1 ? 2 : 0) + (n > 2 ? 1 : 0));     // K0 landed
+    read_k(0);
+    qk(s_v);
+    if (n > 3) {
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      issue_k(3);                                              // K3 shares the ring slot of K0
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mask_and_max(0, true);
+
+    // Steady state for tile j: the logits of tile j sit in s_v.  While the matrix cores
+    // compute the logits of tile j+1, the vector ALUs turn s_v into P(j); then P(j) V(j)
+    // runs on the matrix cores while the row maxima of tile j+1 are taken.  Loads issued
+    // in iteration i are V(i+2) then K(i+4), so at the top of iteration j the operations
+    // younger than the needed V(j) and K(j+1) are K(j+2), V(j+1), K(j+3).
+    int j = 0;
+    // iterations whose loads all exist and whose next tile cannot be the shifted one: no branches
+    for (; j + 4 < n; ++j) {
+      asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+      read_v(j);
+      read_k(j + 1);
+      lazy_rescale();
+      floatx16 s_next[RB];
+      exp_and_pack(j);
+      qk(s_next);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {             // one matrix op, then its share of the softmax ALU work
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, RB * 4, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // both ring slots read above are in registers now
+      issue_v(j + 2);
+      issue_k(j + 4);
+      __builtin_amdgcn_sched_barrier(0);
+      pv();
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) s_v[rb] = s_next[rb];
+      mask_and_max(j + 1, false);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+        __builtin_amdgcn_sched_group_barrier(0x002, RB, 1);
+      }
+    }
+    // the last (up to four) iterations: loads and the next tile exist only conditionally
+    for (; j < n; ++j) {
+      wait_vm_groups((j + 2 < n ? 1 : 0) + (j + 1 < n ? 1 : 0) + (j + 3 < n ? 1 : 0));
+      read_v(j);
+      const bool has_next = j + 1 < n;
+      if (has_next) read_k(j + 1);
+      lazy_rescale();
+      exp_and_pack(j);
+      if (has_next) {
+        floatx16 s_next[RB];
+        qk(s_next);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (j + 2 < n) issue_v(j + 2);
+        if (j + 4 < n) issue_k(j + 4);
+        __builtin_amdgcn_sched_barrier(0);
+        pv();
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) s_v[rb] = s_next[rb];
+        mask_and_max(j + 1, true);
+      } else {
+        pv();
       }
     }
   }

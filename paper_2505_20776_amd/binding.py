@@ -12,7 +12,9 @@ import ctypes
 import os
 from typing import Optional
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspecext.so")
+# SPECEXT_LIBRARY may name another build of the same library (e.g. one compiled with other flags)
+_LIB_PATH = os.environ.get("SPECEXT_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                              "libspecext.so")
 
 SPECEXT_F32 = 0
 SPECEXT_BF16 = 1

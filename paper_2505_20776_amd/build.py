@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libspecext.so")
-SOURCES = ["api.hip", "prefix_generic.hip", "prefix_mfma.hip", "tree_merge.hip", "retrieval.hip"]
+SOURCES = ["api.hip", "prefix_generic.hip", "prefix_mfma.hip", "prefix_mfma_rows.hip", "tree_merge.hip", "retrieval.hip"]
 
 
 def hipcc_path() -> str:

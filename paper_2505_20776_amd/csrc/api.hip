@@ -81,13 +81,23 @@ int resolve(const specext_desc* d, AttnParams* p) {
     if (s < 0 || s % 8 != 0) return SPECEXT_ERR_UNSUPPORTED;
   if (p->q_sh < p->d || p->kp_sl < p->d || p->kt_st < p->d || p->o_sh < p->d) return SPECEXT_ERR_INVALID_ARG;
 
-  // Which prefix kernel runs: the matrix-core kernel takes bf16, d = 128 and, when
-  // scores are wanted, chunk sizes that are whole 32-key tiles.
-  p->use_mfma = (p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L >= 32 &&
-                 (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX))
-                    ? 1
-                    : 0;
-  p->rows_per_group = p->use_mfma ? (p->M > 32 ? 64 : 32) : 64;
+  // Which prefix kernel runs.  The matrix-core kernels take bf16, d = 128, at least one
+  // full 32-key tile and, when scores are wanted, chunk sizes that are whole tiles.
+  // Up to 64 query rows per KV head: the key-split kernel (the four waves of a
+  // workgroup share the rows and split the keys).  More rows: the row-split kernel
+  // (a workgroup owns 128 or 256 rows, so each K/V byte enters one compute unit only).
+  const bool mfma_ok = p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L >= 32 &&
+                       (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX);
+  if (!mfma_ok) {
+    p->use_mfma = 0;
+    p->rows_per_group = 64;
+  } else if (p->M <= 64) {
+    p->use_mfma = 1;
+    p->rows_per_group = p->M > 32 ? 64 : 32;
+  } else {
+    p->use_mfma = 2;
+    p->rows_per_group = p->M > 128 ? 256 : 128;
+  }
   p->score_gran = p->use_mfma ? 32 : p->B;
   p->n_sub = p->want_scores ? (p->L + p->score_gran - 1) / p->score_gran : 0;
 
@@ -100,7 +110,7 @@ int resolve(const specext_desc* d, AttnParams* p) {
     p->keys_per_split = 128;
     return SPECEXT_OK;
   }
-  int64_t unit = p->use_mfma ? 128 : 64;
+  int64_t unit = p->use_mfma == 1 ? 128 : 64;
   if (p->want_scores) unit = unit / gcd64(unit, p->B) * p->B;
   int want = d->num_splits;
   if (want == 0) {
@@ -205,7 +215,9 @@ int specext_verify_attn(const specext_desc* desc, const void* q, const void* k_p
   bind_workspace(&p, w, workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (p.S > 0) {
-    const hipError_t e = prefix_mfma_supports(p) ? launch_prefix_mfma(p, s) : launch_prefix_generic(p, s);
+    const hipError_t e = p.use_mfma == 2   ? launch_prefix_mfma_rows(p, s)
+                         : p.use_mfma == 1 ? launch_prefix_mfma(p, s)
+                                           : launch_prefix_generic(p, s);
     if (e != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
   }
   if (desc->flags & SPECEXT_FLAG_PREFIX_ONLY) return SPECEXT_OK;

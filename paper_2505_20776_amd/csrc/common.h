@@ -37,7 +37,8 @@ struct AttnParams {
   int32_t Hq, Hkv, G, d, L, T, M;
   int32_t B, C, S, keys_per_split, want_scores;
   int32_t score_gran, n_sub;      // keys per score block (32 on the MFMA path, else B) and their count
-  int32_t use_mfma, rows_per_group;
+  int32_t use_mfma;               // 0 vector-ALU kernel, 1 matrix-core key-split kernel, 2 matrix-core row-split kernel
+  int32_t rows_per_group;         // query rows of one KV head that one workgroup covers
   int32_t in_dtype, out_dtype;
   float scale_log2;
   int64_t q_st, q_sh, kp_sh, kp_sl, kt_sh, kt_st, o_st, o_sh;
@@ -45,8 +46,8 @@ struct AttnParams {
 
 // Launchers (each returns a hipError_t from the launch itself).
 hipError_t launch_prefix_generic(const AttnParams& p, hipStream_t stream);
-hipError_t launch_prefix_mfma(const AttnParams& p, hipStream_t stream);
-bool prefix_mfma_supports(const AttnParams& p);
+hipError_t launch_prefix_mfma(const AttnParams& p, hipStream_t stream);        // key-split kernel (use_mfma == 1)
+hipError_t launch_prefix_mfma_rows(const AttnParams& p, hipStream_t stream);   // row-split kernel (use_mfma == 2)
 hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream);
 hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, float* scores, hipStream_t stream);
 hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int32_t* idx_out,

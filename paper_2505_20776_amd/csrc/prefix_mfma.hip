@@ -471,8 +471,6 @@ hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
 
 }  // namespace
 
-bool prefix_mfma_supports(const AttnParams& p) { return p.use_mfma != 0; }
-
 hipError_t launch_prefix_mfma(const AttnParams& p, hipStream_t stream) {
   if (p.S <= 0) return hipSuccess;
   if (p.rows_per_group == 64) {

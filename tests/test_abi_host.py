@@ -58,8 +58,10 @@ def test_workspace_and_splits(sx):
     assert 1 <= sx.num_splits(d) <= 7
     d = _good(sx, prefix_len=0)
     assert sx.num_splits(d) == 0 and sx.workspace_bytes(d) > 0
-    d = _good(sx, prefix_len=100, num_splits=200)
-    assert sx.num_splits(d) == 1                        # matrix-core kernel: 128-key granule
+    d = _good(sx, prefix_len=300, num_splits=200, n_tree=8)
+    assert sx.num_splits(d) == 3                        # matrix-core key-split kernel: 128-key granule
+    d = _good(sx, prefix_len=300, num_splits=200)
+    assert sx.num_splits(d) == 5                        # matrix-core row-split kernel: 64-key granule
     d = _good(sx, prefix_len=100, num_splits=200, flags=sx.SPECEXT_FLAG_VALU_PREFIX)
     assert sx.num_splits(d) == 2                        # vector-ALU kernel: 64-key granule
 

@@ -10,6 +10,10 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libspecext.so")
+# per-source extra flags: both matrix-core kernels are compiled with the matrix-core results in
+# architectural VGPRs (the softmax reads them with vector ALU instructions, which cannot read AGPRs)
+EXTRA_FLAGS = {"prefix_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+               "prefix_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 SOURCES = ["api.hip", "prefix_generic.hip", "prefix_mfma.hip", "prefix_mfma_rows.hip", "tree_merge.hip", "retrieval.hip"]
 
 
@@ -27,7 +31,6 @@ def build_library(verbose: bool = True) -> str:
     common = [
         hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-mllvm", "-amdgpu-mfma-vgpr-form",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
     ]
     procs = []
@@ -35,7 +38,7 @@ def build_library(verbose: bool = True) -> str:
     for src in SOURCES:
         obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
         objs.append(obj)
-        procs.append((src, subprocess.Popen(common + ["-c", os.path.join(CSRC, src), "-o", obj],
+        procs.append((src, subprocess.Popen(common + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj],
                                             stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
     for src, pr in procs:

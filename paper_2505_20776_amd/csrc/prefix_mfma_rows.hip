@@ -34,7 +34,10 @@ constexpr int kTile = 32;                         // keys per tile
 constexpr int kD = 128;                           // head_dim this kernel is written for
 constexpr int kRowBytes = kD * 2;                 // one bf16 K or V row in LDS
 constexpr int kTileBytes = kTile * kRowBytes;     // 8 KB
-constexpr int kRing = 8;                          // tiles per ring (K ring and V ring)
+#ifndef SPECEXT_ROWS_RING
+#define SPECEXT_ROWS_RING 4
+#endif
+constexpr int kRing = SPECEXT_ROWS_RING;          // tiles per ring (K ring and V ring)
 constexpr int kLdsBytes = 2 * kRing * kTileBytes; // 128 KB
 
 template <int RB, bool SCORES>
@@ -58,26 +61,10 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_rows_kernel(AttnParams p) 
   const unsigned char* kbase = static_cast<const unsigned char*>(p.kp) + static_cast<int64_t>(g) * p.kp_sh * 2;
   const unsigned char* vbase = static_cast<const unsigned char*>(p.vp) + static_cast<int64_t>(g) * p.kp_sh * 2;
 
-  // ---- Q fragments (B operand of S^T): lane = row c32, 8 consecutive d per k-step ----
+  // ---- Q fragments (B operand of S^T): lane = row c32, 8 consecutive d per k-step.
+  // Loaded with inline assembly further down (after the first K tile has been
+  // requested) so that waiting for them does not also wait for the tile prefetch.
   bf16x8 qf[RB][8];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int m = row0 + 32 * rb + c32;
-    const bool ok = m < p.M;
-    const int t = ok ? m / p.G : 0;
-    const int h = g * p.G + (ok ? m % p.G : 0);
-    const uint16_t* qp = static_cast<const uint16_t*>(p.q) + t * p.q_st + h * p.q_sh + 8 * hf;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      uintx4 w = {0u, 0u, 0u, 0u};
-      if (ok) w = *reinterpret_cast<const uintx4*>(qp + 16 * ks);
-      qf[rb][ks] = __builtin_bit_cast(bf16x8, w);
-    }
-  }
-  // All query loads have landed before the main loop starts; said through the builtin
-  // so that the compiler's own wait bookkeeping sees it and adds no vmcnt wait of its
-  // own inside the loop (0x0F70 = vmcnt(0), other counters untouched).
-  __builtin_amdgcn_s_waitcnt(0x0F70);
 
   // ---- LDS rings.  A tile is 32 rows x 256 B; one direct load writes 1 KB = 4
   // consecutive rows, lane i landing at byte 16*i.  The 16-byte chunks of a row are
@@ -152,6 +139,19 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_rows_kernel(AttnParams p) 
     }
   };
 
+  // single-fragment forms of the two reads, for the pipelined loop that streams them
+  auto read_k_frag = [&](const unsigned char* kst, int ks) {
+    const uintx4 kw = *reinterpret_cast<const uintx4*>(kst + (((2 * ks) ^ k_rd_xor) << 4));
+    return __builtin_bit_cast(bf16x8, kw);
+  };
+  auto read_v_frag = [&](const unsigned char* vst, int v) {          // v = 2 * db + jj
+    const unsigned char* col = vst + (((v >> 1) ^ v_q4) << 6);
+    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(col + (16 * (v & 1)) * kRowBytes));
+    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(col + (16 * (v & 1) + 8) * kRowBytes));
+    const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  };
+
   floatx16 acc_o[4][RB];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
@@ -168,30 +168,29 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_rows_kernel(AttnParams p) 
   const float c = p.scale_log2;
   const float lazy_raw = kLazyLog2 / c;      // the lazy margin in raw-logit units
 
-  floatx16 s_v[RB];        // logits of the tile whose softmax comes next
   float tile_max[RB];
   bf16x8 pf[RB][2];
 
-  auto mask_and_max = [&](int t, bool may_be_shifted) {
-    if (may_be_shifted) {
-      const int key0 = tile_key0(t);
-      const int first_row = tile_first_row(t);
-      if (first_row < key0) {
+  auto mask_shifted = [&](floatx16 (&sv)[RB], int t) {
+    const int key0 = tile_key0(t);
+    const int first_row = tile_first_row(t);
+    if (first_row < key0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = first_row + 8 * (r >> 2) + 4 * hf + (r & 3);
-          if (key < key0) {
+      for (int r = 0; r < 16; ++r) {
+        const int key = first_row + 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (key < key0) {
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) s_v[rb][r] = -INFINITY;
-          }
+          for (int rb = 0; rb < RB; ++rb) sv[rb][r] = -INFINITY;
         }
       }
     }
+  };
+  auto row_max = [&](const floatx16 (&sv)[RB]) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float mx = fmaxf(s_v[rb][0], s_v[rb][1]);
+      float mx = fmaxf(sv[rb][0], sv[rb][1]);
 #pragma unroll
-      for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s_v[rb][r], s_v[rb][r + 1]));
+      for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sv[rb][r], sv[rb][r + 1]));
       tile_max[rb] = mx;
     }
   };
@@ -214,40 +213,39 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_rows_kernel(AttnParams p) 
       }
     }
   };
-  auto exp_and_pack = [&](int t) {
+  auto store_score_block = [&](int rb, float part, float mc, int t) {
+    const float tot = part + __shfl_xor(part, 32, 64);
+    const int m = row0 + 32 * rb + c32;
+    if (hf == 0 && m < p.M) {
+      float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + tile_key0(t) / kTile) * p.M + m) * 2;
+      *reinterpret_cast<floatx2*>(cp) = floatx2{tot, mc};
+    }
+  };
+  // exponentials of sv against the references -> P^T fragments, row sums, score blocks
+  auto exp_and_pack = [&](floatx16 (&sv)[RB], int t) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       const float mc = ref[rb] * c;
       float part = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float pr = fast_exp2(fmaf(s_v[rb][r], c, -mc));
-        s_v[rb][r] = pr;
+        const float pr = fast_exp2(fmaf(sv[rb][r], c, -mc));
+        sv[rb][r] = pr;
         part += pr;
       }
       run_sum[rb] += part;
-      if (SCORES) {
-        const float tot = part + __shfl_xor(part, 32, 64);
-        const int m = row0 + 32 * rb + c32;
-        if (hf == 0 && m < p.M) {
-          float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + tile_key0(t) / kTile) * p.M + m) * 2;
-          *reinterpret_cast<floatx2*>(cp) = floatx2{tot, mc};
-        }
-      }
-      pf[rb][0] = pack8(s_v[rb], 0);
-      pf[rb][1] = pack8(s_v[rb], 8);
+      if (SCORES) store_score_block(rb, part, mc, t);
+      pf[rb][0] = pack8(sv[rb], 0);
+      pf[rb][1] = pack8(sv[rb], 8);
     }
   };
+  const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   auto qk = [&](floatx16 (&acc_s)[RB]) {
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc_s[rb][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
-        acc_s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], acc_s[rb], 0, 0, 0);
+        acc_s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], ks == 0 ? zero16 : acc_s[rb], 0, 0, 0);
   };
   auto pv = [&]() {
 #pragma unroll
@@ -259,54 +257,125 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_rows_kernel(AttnParams p) 
           acc_o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][jj], pf[rb][jj], acc_o[db][rb], 0, 0, 0);
   };
 
+  // One pipelined tile step with the instruction order pinned by scheduling barriers
+  // (a lone wave per SIMD overlaps matrix and vector work only if the two kinds of
+  // instruction alternate in its stream): the 8*RB matrix ops of the logits of tile
+  // t+1 (into nxt) alternate with the exponentials of tile t (in cur), two values per
+  // matrix op; then the 8*RB matrix ops of P(t) V(t) alternate with the row maxima of nxt.
+  auto pipelined_step = [&](floatx16 (&cur)[RB], floatx16 (&nxt)[RB], int t) {
+    const unsigned char* kst = kring + ((t + 1) % kRing) * kTileBytes + k_rd_base;
+    const unsigned char* vst = vring + (t % kRing) * kTileBytes + v_rd_base;
+    float mc[RB], part[RB];
+    uintx4 pw[RB][2];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      mc[rb] = ref[rb] * c;
+      part[rb] = 0.f;
+    }
+    bf16x8 kq[3], vq[3];           // operand fragments, read from LDS two steps ahead of their use
+    kq[0] = read_k_frag(kst, 0);
+    kq[1] = read_k_frag(kst, 1);
+#pragma unroll
+    for (int i = 0; i < 8 * RB; ++i) {
+      const int ks = i / RB, rbm = i % RB;
+      if (rbm == 0 && ks + 2 < 8) kq[(ks + 2) % 3] = read_k_frag(kst, ks + 2);
+      if (i == 8 * RB - 2) vq[0] = read_v_frag(vst, 0);
+      if (i == 8 * RB - 1) vq[1] = read_v_frag(vst, 1);
+      nxt[rbm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kq[ks % 3], qf[rbm][ks], ks == 0 ? zero16 : nxt[rbm], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      const int rb = i / 8, r = 2 * (i % 8);
+      const float p0 = fast_exp2(fmaf(cur[rb][r], c, -mc[rb]));
+      const float p1 = fast_exp2(fmaf(cur[rb][r + 1], c, -mc[rb]));
+      part[rb] += p0 + p1;
+      const floatx2 f2 = {p0, p1};
+      pw[rb][r / 8][(r % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2));
+      if (i % 8 == 7) {
+        run_sum[rb] += part[rb];
+        if (SCORES) store_score_block(rb, part[rb], mc[rb], t);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      pf[rb][0] = __builtin_bit_cast(bf16x8, pw[rb][0]);
+      pf[rb][1] = __builtin_bit_cast(bf16x8, pw[rb][1]);
+    }
+    float mx[RB];
+#pragma unroll
+    for (int i = 0; i < 8 * RB; ++i) {
+      const int v = i / RB, rbm = i % RB;
+      if (rbm == 0 && v + 2 < 8) vq[(v + 2) % 3] = read_v_frag(vst, v + 2);
+      acc_o[v >> 1][rbm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vq[v % 3], pf[rbm][v & 1], acc_o[v >> 1][rbm], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      const int rb = i / 8, r = 2 * (i % 8);
+      mx[rb] = r == 0 ? fmaxf(nxt[rb][0], nxt[rb][1]) : fmaxf(mx[rb], fmaxf(nxt[rb][r], nxt[rb][r + 1]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) tile_max[rb] = mx[rb];
+  };
+
   // Each wave's loads form the sequence K0 V0 K1 V1 ... (two instructions per entry;
   // K(t) has index 2t, V(t) index 2t+1).  Before iteration j every entry with index
   // <= min(2(j + kRing - 1), 2n - 1) has been issued.
   auto last_issued = [&](int j) { return min(2 * (j + kRing - 1), 2 * n - 1); };
 
-  // prologue: K(t), V(t) for t < kRing-1, then K(kRing-1); logits of tile 0
+  // prologue: K0 first, then the queries, then V0 K1 V1 ... K(kRing-1)
+  issue_k(0);
 #pragma unroll
-  for (int t = 0; t < kRing - 1; ++t) {
+  for (int rb = 0; rb < RB; ++rb) {
+    const int m = min(row0 + 32 * rb + c32, p.M - 1);       // padding rows repeat the last real row (never stored)
+    const int t = m / p.G;
+    const int h = g * p.G + m % p.G;
+    const uint16_t* qp = static_cast<const uint16_t*>(p.q) + t * p.q_st + h * p.q_sh + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qf[rb][ks]) : "v"(qp + 16 * ks) : "memory");
+  }
+  int issued_after_q = 0;                 // load instructions younger than the query loads
+  if (0 < n) {
+    issue_v(0);
+    issued_after_q += 2;
+  }
+#pragma unroll
+  for (int t = 1; t < kRing; ++t) {
     if (t < n) {
       issue_k(t);
-      issue_v(t);
+      issued_after_q += 2;
+      if (t < kRing - 1) {
+        issue_v(t);
+        issued_after_q += 2;
+      }
     }
   }
-  if (kRing - 1 < n) issue_k(kRing - 1);
-  wait_vmcnt_even(2 * last_issued(0));          // this wave's part of K0 has landed
-  lds_barrier();                                // ... and so has everybody's
+  // K0 and the queries have landed (everything older than the loads counted above);
+  // the fragments are operands of the wait so that no use of them can move above it
+  wait_vmcnt_even(issued_after_q);
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+    asm volatile("" : "+v"(qf[rb][0]), "+v"(qf[rb][1]), "+v"(qf[rb][2]), "+v"(qf[rb][3]), "+v"(qf[rb][4]),
+                      "+v"(qf[rb][5]), "+v"(qf[rb][6]), "+v"(qf[rb][7]) :: "memory");
+  lds_barrier();                                // everybody's part of K0 has landed
   read_k(0);
-  qk(s_v);
-  mask_and_max(0, true);
+  floatx16 s_a[RB], s_b[RB];       // logits of the current / the next tile, swapping roles
+  qk(s_a);
+  if (n == 1) mask_shifted(s_a, 0);
+  row_max(s_a);
 
-  int j = 0;
-  // iterations in which every load still exists and tile j+1 is not the split's last: no branches
-  for (; j + kRing < n; ++j) {
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(4 * (kRing - 2)) : "memory");   // own parts of V(j), K(j+1) landed
-    lds_barrier();                   // all parts landed; everyone is done with the slots of V(j-1) and K(j)
-    issue_v(j - 1 + kRing);
-    issue_k(j + kRing);
-    read_v(j);
-    read_k(j + 1);
+  auto top_of_iteration = [&](int jj) {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(4 * (kRing - 2)) : "memory");   // own parts of V(jj), K(jj+1) landed
+    lds_barrier();                   // all parts landed; everyone is done with the slots of V(jj-1) and K(jj)
+    issue_v(jj - 1 + kRing);
+    issue_k(jj + kRing);
     lazy_rescale();
-    floatx16 s_next[RB];
-    exp_and_pack(j);
-    qk(s_next);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {             // one matrix op, then its share of the softmax ALU work
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, RB * 4, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    pv();
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) s_v[rb] = s_next[rb];
-    mask_and_max(j + 1, false);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-      __builtin_amdgcn_sched_group_barrier(0x002, RB, 1);
-    }
+  };
+  int j = 0;
+  // steady state, two tiles per trip: every load still exists and no tile is the split's last
+  for (; j + 1 + kRing < n; j += 2) {
+    top_of_iteration(j);
+    pipelined_step(s_a, s_b, j);
+    top_of_iteration(j + 1);
+    pipelined_step(s_b, s_a, j + 1);
   }
   // the remaining iterations: loads run out, the last tile may be shifted
   for (; j < n; ++j) {
@@ -319,14 +388,14 @@ __global__ __launch_bounds__(kWaves * 64) void prefix_rows_kernel(AttnParams p) 
     read_v(j);
     if (has_next) read_k(j + 1);
     lazy_rescale();
-    exp_and_pack(j);
+    exp_and_pack(s_a, j);
     if (has_next) {
-      floatx16 s_next[RB];
-      qk(s_next);
+      qk(s_b);
       pv();
+      if (j + 2 == n) mask_shifted(s_b, j + 1);
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) s_v[rb] = s_next[rb];
-      mask_and_max(j + 1, true);
+      for (int rb = 0; rb < RB; ++rb) s_a[rb] = s_b[rb];
+      row_max(s_a);
     } else {
       pv();
     }

@@ -84,20 +84,54 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
     a = (par >= a || par < -1) ? -1 : par;   // a malformed entry ends the walk (node treated as a root)
   }
 
-  // prefix splits, in split order
-  for (int s = 0; s < p.S; ++s) {
-    const int64_t slot = static_cast<int64_t>(s) * n_rows + row;
-    const float ms = p.part_ml[slot * 2];
-    const float ls = p.part_ml[slot * 2 + 1];
-    if (!(ls > 0.f)) continue;       // empty split
-    const float new_max = fmaxf(run_max, ms);
-    const float alpha = exp2f(run_max - new_max);
-    const float beta = exp2f(ms - new_max);
-    const float* po = p.part_o + slot * D + lane * E;
+  // prefix splits.  Lane s first takes (max, sum) of split s (64 splits per round), the
+  // wave agrees on the common maximum, and lane s keeps the weight exp2(max_s - max_total)
+  // of its split.  The partial outputs are then added in split order with the weights
+  // broadcast from their lanes; the loads do not depend on one another, so several
+  // are in flight at once.  Fixed order, no atomics: bit-reproducible.
+  for (int s0 = 0; s0 < p.S; s0 += 64) {
+    const int s_mine = s0 + lane;
+    float ms = -INFINITY, ls = 0.f;
+    if (s_mine < p.S) {
+      const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(s_mine) * n_rows + row) * 2);
+      if (ml.y > 0.f) {              // an empty split contributes nothing
+        ms = ml.x;
+        ls = ml.y;
+      }
+    }
+    float round_max = ms;
 #pragma unroll
-    for (int e = 0; e < E; ++e) o[e] = fmaf(po[e], beta, o[e] * alpha);
-    run_sum = fmaf(ls, beta, run_sum * alpha);
+    for (int off = 32; off > 0; off >>= 1) round_max = fmaxf(round_max, __shfl_xor(round_max, off, 64));
+    const float new_max = fmaxf(run_max, round_max);
+    if (new_max == -INFINITY) continue;          // nothing so far and nothing in this round (wave-uniform)
+    const float alpha = exp2f(run_max - new_max);
+    const float w = ls > 0.f ? exp2f(ms - new_max) : 0.f;
     run_max = new_max;
+    run_sum = fmaf(run_sum, alpha, wave_sum(ls * w));
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] *= alpha;
+    const int s_end = min(64, p.S - s0);
+    const float* po = p.part_o + (static_cast<int64_t>(s0) * n_rows + row) * D + lane * E;
+    const int64_t split_stride = static_cast<int64_t>(n_rows) * D;
+    int s = 0;
+    for (; s + 8 <= s_end; s += 8) {
+      float v[8][E];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[u][e] = po[(s + u) * split_stride + e];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), s + u));
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] = fmaf(v[u][e], wu, o[e]);
+      }
+    }
+    for (; s < s_end; ++s) {
+      const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), s));
+#pragma unroll
+      for (int e = 0; e < E; ++e) o[e] = fmaf(po[s * split_stride + e], wu, o[e]);
+    }
   }
 
   const float inv = 1.f / run_sum;

@@ -36,7 +36,13 @@ constexpr int kTileBytes = kTile * kRowBytes;     // 8 KB
 #define SPECEXT_ROWS_RING 4
 #endif
 constexpr int kRing = SPECEXT_ROWS_RING;          // tiles per ring (K ring and V ring)
-constexpr int kLdsBytes = 2 * kRing * kTileBytes;
+constexpr int kPatchStride = 64 + 4;              // floats per row of the output staging patch (padded against bank conflicts)
+constexpr int kRingBytes = 2 * kRing * kTileBytes;
+constexpr int lds_bytes(int waves) { return kRingBytes > waves * 32 * kPatchStride * 4 ? kRingBytes : waves * 32 * kPatchStride * 4; }
+#ifndef SPECEXT_ROWS_SKEW
+#define SPECEXT_ROWS_SKEW 0
+#endif
+constexpr bool kSkewHalves = SPECEXT_ROWS_SKEW != 0;   // upper half of the waves runs half a tile behind
 
 template <int WAVES, bool SCORES>
 __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
@@ -99,7 +105,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     }
   };
 
-  // prologue: the first kRing-1 tiles are requested, and in between the queries
+  // prologue: the first kRing-2 tiles are requested, and in between the queries
   // (B operand of S^T: lane = row c32, 8 consecutive d per k-step) with plain loads
   // in inline assembly, so that waiting for them does not drain the tile prefetch
   issue_tile(0);
@@ -114,7 +120,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   }
   int younger = 0;                                // load instructions issued after the query loads
 #pragma unroll
-  for (int t = 1; t < kRing - 1; ++t) {
+  for (int t = 1; t < kRing - 2; ++t) {
     if (t < n) {
       issue_tile(t);
       younger += 2 * kLoadsPerWave;
@@ -145,31 +151,33 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const float lazy_raw = kLazyLog2 / c;      // the lazy margin in raw-logit units
   const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  // Each wave's loads form the sequence K0 V0 K1 V1 ... (kLoadsPerWave instructions
-  // per entry).  Before iteration j the tiles up to min(j + kRing - 2, n - 1) have
-  // been requested; tile j is needed, so 2 * kLoadsPerWave instructions per younger
-  // tile may stay in flight.
-  for (int j = 0; j < n; ++j) {
-    const int younger_tiles = min(j + kRing - 2, n - 1) - j;
-    if (younger_tiles == kRing - 2) {
-      asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kLoadsPerWave * (kRing - 2)) : "memory");
+  // Each wave's loads form the sequence K0 V0 K1 V1 ... (kLoadsPerWave instructions per
+  // entry).  After barrier j every wave is done with tile j-2 (see the skew below), so
+  // tile j-2+kRing is requested into that slot; before iteration j the tiles up to
+  // min(j + kRing - 3, n - 1) have been requested and tile j is needed.
+  auto top = [&](int j) {
+    const int younger_tiles = min(j + kRing - 3, n - 1) - j;
+    if (younger_tiles == kRing - 3) {
+      asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kLoadsPerWave * (kRing - 3)) : "memory");
     } else {
       wait_vmcnt_even(2 * kLoadsPerWave * younger_tiles);
     }
-    lds_barrier();            // every share of tile j has landed; everyone is done with tile j-1
-    if (j + kRing - 1 < n) issue_tile(j + kRing - 1);           // into the slot of tile j-1
+    lds_barrier();            // every share of tile j has landed
+    if (j - 2 + kRing < n) issue_tile(j - 2 + kRing);
+  };
 
-    // ---- S^T = K Q^T ----
+  floatx16 s;                  // logits, then probabilities, of the tile in flight
+  bf16x8 vf[4][2];             // its V^T fragments
+  // first half of a tile: logits, V^T fragments requested, shifted-tile mask
+  auto logits = [&](int j) {
     const unsigned char* kst = kring + (j % kRing) * kTileBytes + k_rd_base;
-    floatx16 s = zero16;
+    s = zero16;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       const uintx4 kw = *reinterpret_cast<const uintx4*>(kst + (((2 * ks) ^ k_rd_xor) << 4));
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[ks], s, 0, 0, 0);
     }
-    // ---- V^T fragments requested early; they are consumed after the softmax ----
     const unsigned char* vst = vring + (j % kRing) * kTileBytes + v_rd_base;
-    bf16x8 vf[4][2];
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
       const unsigned char* col = vst + ((db ^ v_q4) << 6);
@@ -181,19 +189,19 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
         vf[db][jj] = __builtin_bit_cast(bf16x8, both);
       }
     }
-
-    // ---- rows of a shifted last tile that belong to the tile before ----
     const int key0 = tile_key0(j);
     const int first_row = tile_first_row(j);
-    if (first_row < key0) {
+    if (first_row < key0) {          // rows of a shifted last tile that belong to the tile before
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = first_row + 8 * (r >> 2) + 4 * hf + (r & 3);
         if (key < key0) s[r] = -INFINITY;
       }
     }
-
-    // ---- online softmax, one query row per lane pair; the reference moves lazily ----
+  };
+  // second half: online softmax (one query row per lane pair, the reference moves
+  // lazily), then O^T += V^T P^T
+  auto softmax_pv = [&](int j) {
     float mx = fmaxf(s[0], s[1]);
 #pragma unroll
     for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[r], s[r + 1]));
@@ -219,43 +227,81 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     if (SCORES) {
       const float tot = part + __shfl_xor(part, 32, 64);
       if (hf == 0 && m < p.M) {
-        float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + key0 / kTile) * p.M + m) * 2;
+        float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + tile_key0(j) / kTile) * p.M + m) * 2;
         *reinterpret_cast<floatx2*>(cp) = floatx2{tot, mc};
       }
     }
     const bf16x8 pf0 = pack8(s, 0);
     const bf16x8 pf1 = pack8(s, 8);
-
-    // ---- O^T += V^T P^T ----
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
       acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][0], pf0, acc_o[db], 0, 0, 0);
       acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][1], pf1, acc_o[db], 0, 0, 0);
     }
+  };
+
+  // The waves of the upper half of the workgroup run half a tile behind the lower
+  // half: between two barriers the lower half does logits(j) then softmax_pv(j), the
+  // upper half softmax_pv(j-1) then logits(j).  The two waves that share a SIMD (w and
+  // w + WAVES/2) are thus in different phases, and one's matrix work overlaps the
+  // other's vector work.  Both halves pass the same n barriers.
+  if (!kSkewHalves || wave < WAVES / 2) {
+    for (int j = 0; j < n; ++j) {
+      top(j);
+      logits(j);
+      softmax_pv(j);
+    }
+  } else {
+    top(0);
+    logits(0);
+    for (int j = 1; j < n; ++j) {
+      top(j);
+      softmax_pv(j - 1);
+      logits(j);
+    }
+    softmax_pv(n - 1);
   }
 
-  // ---- partial results of this split: unnormalised O, reference (base-2 units) and row sum ----
+  // ---- partial results of this split: unnormalised O, reference (base-2 units) and row sum.
+  // O^T sits in registers with a lane owning one row; it goes through a wave-private
+  // LDS patch (two halves of 64 columns) so that the global stores are 256-byte runs.
   const float l_tot = run_sum + __shfl_xor(run_sum, 32, 64);
-  if (m < p.M) {
-    const int64_t slot = static_cast<int64_t>(split) * p.Hq * p.T + g * p.M + m;
+  lds_barrier();                                   // every wave is done with the tile rings
+  float* patch = reinterpret_cast<float*>(lds) + wave * (32 * kPatchStride);
+  const int64_t slot0 = static_cast<int64_t>(split) * p.Hq * p.T + g * p.M + row0;     // slot of the wave's first row
+  const int rows_here = min(32, p.M - row0);       // <= 0 for a wave of padding rows only
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      float* po = p.part_o + slot * kD + 32 * db + 4 * hf;
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int d2 = 0; d2 < 2; ++d2) {
+      const int db = 2 * half + d2;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4)
-        *reinterpret_cast<floatx4*>(po + 8 * r4) =
+        *reinterpret_cast<floatx4*>(patch + c32 * kPatchStride + 32 * d2 + 8 * r4 + 4 * hf) =
             floatx4{acc_o[db][4 * r4], acc_o[db][4 * r4 + 1], acc_o[db][4 * r4 + 2], acc_o[db][4 * r4 + 3]};
     }
-    if (hf == 0) {
-      p.part_ml[slot * 2] = ref * c;
-      p.part_ml[slot * 2 + 1] = l_tot;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = 4 * it + (lane >> 4);
+      const floatx4 v = *reinterpret_cast<const floatx4*>(patch + row * kPatchStride + 4 * (lane & 15));
+      if (row < rows_here)
+        *reinterpret_cast<floatx4*>(p.part_o + (slot0 + row) * kD + 64 * half + 4 * (lane & 15)) = v;
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (hf == 0 && m < p.M) {
+    p.part_ml[(slot0 + c32) * 2] = ref * c;
+    p.part_ml[(slot0 + c32) * 2 + 1] = l_tot;
   }
 }
 
 template <int WAVES, bool SCORES>
 hipError_t launch_rows(const AttnParams& p, hipStream_t stream) {
   auto kernel = prefix_rows_kernel<WAVES, SCORES>;
+  constexpr int kLdsBytes = lds_bytes(WAVES);
   if (kLdsBytes > 64 * 1024) {
     // more than the default 64 KB of dynamic LDS: raise the cap once per device
     static std::atomic<bool> attr_set[64];

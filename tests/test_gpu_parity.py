@@ -94,6 +94,8 @@ SHAPES = [
     ("bf16", 32, 8, 128, 65, "single", 32),
     ("bf16", 32, 8, 128, 4096 + 13, "wide128", 64),
     ("bf16", 32, 8, 128, 3000, "chain16", 64),
+    ("bf16", 32, 8, 128, 2100, "eagle30", 32),      # 120 rows per KV head: 4-wave row-split kernel
+    ("bf16", 32, 8, 128, 40, "eagle30", 32),        # barely more than one tile
     ("bf16", 8, 8, 128, 1500, "eagle60", 32),       # G = 1
     ("bf16", 16, 2, 128, 1111, "rand8", 32),        # G = 8
     ("bf16", 8, 2, 64, 2049, "eagle60", 32),        # head_dim 64
@@ -104,7 +106,8 @@ SHAPES = [
 
 
 def _tree(kind, rng):
-    return {"eagle60": lambda: eagle_style_tree(60, 6, rng), "single": lambda: chain_tree(1),
+    return {"eagle60": lambda: eagle_style_tree(60, 6, rng), "eagle30": lambda: eagle_style_tree(30, 5, rng),
+            "single": lambda: chain_tree(1),
             "wide128": lambda: wide_tree(128, 4, rng), "chain16": lambda: chain_tree(16),
             "rand8": lambda: random_parent_tree(8, 4, rng)}[kind]()
 

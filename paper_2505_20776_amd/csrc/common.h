@@ -68,10 +68,31 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
   return static_cast<uint16_t>(u >> 16);
 }
 
+// Wave-wide reductions on the vector ALU's data-parallel-primitive paths (no LDS
+// round trips): four steps inside each row of 16 lanes (quad swaps, half mirror,
+// mirror), then the four row totals are read out and combined.  Every lane gets
+// the result.
+#define SPECEXT_DPP(v, ctrl) \
+  __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), (ctrl), 0xf, 0xf, false))
+
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
+  v += SPECEXT_DPP(v, 0xB1);    // quad_perm [1,0,3,2]
+  v += SPECEXT_DPP(v, 0x4E);    // quad_perm [2,3,0,1]
+  v += SPECEXT_DPP(v, 0x141);   // row_half_mirror
+  v += SPECEXT_DPP(v, 0x140);   // row_mirror
+  const int b = __float_as_int(v);
+  return (__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
+         (__int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48)));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, SPECEXT_DPP(v, 0xB1));
+  v = fmaxf(v, SPECEXT_DPP(v, 0x4E));
+  v = fmaxf(v, SPECEXT_DPP(v, 0x141));
+  v = fmaxf(v, SPECEXT_DPP(v, 0x140));
+  const int b = __float_as_int(v);
+  return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 0)), __int_as_float(__builtin_amdgcn_readlane(b, 16))),
+               fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 32)), __int_as_float(__builtin_amdgcn_readlane(b, 48))));
 }
 
 }  // namespace specext

@@ -14,27 +14,39 @@ namespace {
 
 // scores[r][c] = (1/Hq) * sum_h  sum_blocks  blocksum(h, t) * exp2(ref - lse2(h, t)) / |c|
 // The prefix pass leaves one (sum, ref) pair per score block (score_gran keys;
-// a chunk is a whole number of blocks).  Heads and blocks are added in
-// ascending order: a fixed-order fp32 sum.
+// a chunk is a whole number of blocks).  A workgroup handles 64 chunks; the heads
+// of a chunk are dealt to four threads (head h goes to thread h mod 4), each adds
+// its heads in ascending order, and the four partial sums are combined in a fixed
+// order: a deterministic fp32 sum.
 __global__ __launch_bounds__(256) void chunk_scores_kernel(AttnParams p, int first_row, float* scores) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  __shared__ float partial[4][64];
+  const int cl = threadIdx.x & 63;
+  const int part = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   const int t = first_row + blockIdx.y;
-  if (c >= p.C) return;
-  const int size = min(p.B, p.L - c * p.B);
-  const int per_chunk = p.B / p.score_gran;
-  const int sub_lo = c * per_chunk;
-  const int sub_hi = min(sub_lo + per_chunk, p.n_sub);
   float acc = 0.f;
-  for (int h = 0; h < p.Hq; ++h) {
-    const int g = h / p.G;
-    const int m = t * p.G + (h - g * p.G);
-    const float l2 = p.lse2[g * p.M + m];
-    for (int sb = sub_lo; sb < sub_hi; ++sb) {
-      const float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sb) * p.M + m) * 2;
-      acc += cp[0] * exp2f(cp[1] - l2);
+  if (c < p.C) {
+    const int per_chunk = p.B / p.score_gran;
+    const int sub_lo = c * per_chunk;
+    const int sub_hi = min(sub_lo + per_chunk, p.n_sub);
+    for (int h = part; h < p.Hq; h += 4) {
+      const int g = h / p.G;
+      const int m = t * p.G + (h - g * p.G);
+      const float l2 = p.lse2[g * p.M + m];
+      for (int sb = sub_lo; sb < sub_hi; ++sb) {
+        const float2 cp = *reinterpret_cast<const float2*>(
+            p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sb) * p.M + m) * 2);
+        acc += cp.x * exp2f(cp.y - l2);
+      }
     }
   }
-  scores[static_cast<int64_t>(blockIdx.y) * p.C + c] = acc / (static_cast<float>(size) * static_cast<float>(p.Hq));
+  partial[part][cl] = acc;
+  __syncthreads();
+  if (part == 0 && c < p.C) {
+    const int size = min(p.B, p.L - c * p.B);
+    const float tot = ((partial[0][cl] + partial[1][cl]) + partial[2][cl]) + partial[3][cl];
+    scores[static_cast<int64_t>(blockIdx.y) * p.C + c] = tot / (static_cast<float>(size) * static_cast<float>(p.Hq));
+  }
 }
 
 // --------------------------------------------------------------------------
@@ -74,56 +86,87 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_sums, int& 
   return base + incl - v;
 }
 
-// One workgroup.  Four rounds of an 8-bit radix select find the key value of
-// the k-th largest score and how many scores are strictly larger; a final
-// pass in index order emits every larger score plus the lowest-indexed ties.
+// Block-wide count of a predicate (up to kSelPerThread flags per thread, bit u of
+// `flags` = flag u); every thread gets the total.  Wave counts come from ballots;
+// `slots` must hold blockDim.x / 64 ints and alternate between two buffers from
+// call to call so that one barrier per call is enough.
+__device__ __forceinline__ int block_count(unsigned flags, int n_flags, int* slots) {
+  int c = 0;
+  for (int u = 0; u < n_flags; ++u) c += __popcll(__ballot((flags >> u) & 1u));
+  if ((threadIdx.x & 63) == 0) slots[threadIdx.x >> 6] = c;
+  __syncthreads();
+  // all sixteen slots are read at once (slots of absent waves hold zero), one LDS round trip
+  const int4 a = *reinterpret_cast<const int4*>(slots), b = *reinterpret_cast<const int4*>(slots + 4),
+             cc = *reinterpret_cast<const int4*>(slots + 8), d = *reinterpret_cast<const int4*>(slots + 12);
+  return ((a.x + a.y) + (a.z + a.w)) + ((b.x + b.y) + (b.z + b.w)) + ((cc.x + cc.y) + (cc.z + cc.w)) +
+         ((d.x + d.y) + (d.z + d.w));
+}
+
+// One workgroup.  The key value V of the k-th largest score is built bit by bit from
+// the top: a bit stays set if at least k keys are >= the candidate.  Scores above V
+// are all taken; of the scores equal to V the lowest-indexed ones fill what is left.
+// A last pass in index order (block scans over the keep flags) writes the output
+// ascending.  Threads hold up to kSelPerThread keys in registers; longer inputs are
+// re-read from memory.
+constexpr int kSelPerThread = 4;
+
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, int n, int k,
                                                             int* __restrict__ idx_out, int* __restrict__ n_out) {
-  __shared__ int hist[256];
+  __shared__ __attribute__((aligned(16))) int slots[2][kSelThreads / 64];
   __shared__ int wave_sums[kSelThreads / 64];
-  __shared__ uint32_t sh_prefix;
-  __shared__ int sh_need;
 
   const int k_eff = min(k, n);
   if (threadIdx.x == 0) *n_out = k_eff;
   for (int i = k_eff + threadIdx.x; i < k; i += blockDim.x) idx_out[i] = -1;
   if (k_eff == 0) return;
+  if (threadIdx.x < 2 * (kSelThreads / 64)) slots[0][threadIdx.x] = 0;      // slots of absent waves stay zero
+  __syncthreads();
 
-  uint32_t prefix = 0;      // high bits fixed so far
-  uint32_t mask = 0;
-  int need = k_eff;         // rank still wanted among keys matching the prefix
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int b = threadIdx.x; b < 256; b += blockDim.x) hist[b] = 0;
-    __syncthreads();
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      const uint32_t key = orderable(scores[i]);
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int above = 0;
-      int b = 255;
-      for (; b > 0; --b) {
-        if (above + hist[b] >= need) break;
-        above += hist[b];
-      }
-      sh_prefix = prefix | (static_cast<uint32_t>(b) << shift);
-      sh_need = need - above;
-    }
-    __syncthreads();
-    prefix = sh_prefix;
-    need = sh_need;
-    mask |= 255u << shift;
-    __syncthreads();
+  const bool in_regs = n <= kSelThreads * kSelPerThread;
+  uint32_t mine[kSelPerThread];
+#pragma unroll
+  for (int u = 0; u < kSelPerThread; ++u) {
+    const int i = u * kSelThreads + threadIdx.x;
+    mine[u] = (in_regs && i < n) ? orderable(scores[i]) : 0u;       // 0 is below every real key
   }
-  // prefix is now the k-th largest key; `need` ties (>= 1) are taken, lowest index first
+  // how many keys are >= cand (block-wide)
+  auto count_ge = [&](uint32_t cand, int* slot) {
+    if (in_regs) {
+      unsigned flags = 0;
+#pragma unroll
+      for (int u = 0; u < kSelPerThread; ++u) flags |= (mine[u] >= cand ? 1u : 0u) << u;
+      const int n_flags = min(kSelPerThread, (n + kSelThreads - 1) / kSelThreads);
+      return block_count(flags, n_flags, slot);
+    }
+    int total = 0;                     // long input: 32 keys per thread per round of ballots
+    for (int base = 0; base < n; base += blockDim.x * 32) {
+      unsigned flags = 0;
+      for (int u = 0; u < 32; ++u) {
+        const int i = base + u * blockDim.x + threadIdx.x;
+        flags |= ((i < n && orderable(scores[i]) >= cand) ? 1u : 0u) << u;
+      }
+      // (an extra barrier keeps the slot buffer of the previous call intact)
+      __syncthreads();
+      total += block_count(flags, 32, slot);
+    }
+    return total;
+  };
+  uint32_t v = 0;
+  int round = 0;
+  for (int bit = 31; bit >= 0; --bit, ++round) {
+    const uint32_t cand = v | (1u << bit);
+    if (count_ge(cand, slots[round & 1]) >= k_eff) v = cand;
+  }
+  // v is the k-th largest key.  Keys above it: n_gt < k_eff; ties needed: k_eff - n_gt >= 1
+  const int n_gt = v == 0xffffffffu ? 0 : count_ge(v + 1u, slots[round & 1]);
+  const int need = k_eff - n_gt;
   int out_base = 0, tie_base = 0;
   for (int start = 0; start < n; start += blockDim.x) {
     const int i = start + threadIdx.x;
     uint32_t key = 0;
     if (i < n) key = orderable(scores[i]);
-    const int is_tie = (i < n && key == prefix) ? 1 : 0;
-    const int is_gt = (i < n && key > prefix) ? 1 : 0;
+    const int is_tie = (i < n && key == v) ? 1 : 0;
+    const int is_gt = (i < n && key > v) ? 1 : 0;
     int tie_total;
     const int tie_rank = tie_base + block_exclusive_scan(is_tie, wave_sums, tie_total);
     const int take = is_gt | (is_tie & (tie_rank < need ? 1 : 0));
@@ -176,36 +219,47 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(const uint4* __restric
 }
 
 // One workgroup: original positions of the kept tokens, -1 behind them, and the total.
+// Entry r of the list is handled by thread r (lists longer than the block go round
+// by round, carrying the running offset), offsets come from a block scan.
 __global__ __launch_bounds__(256) void gather_meta_kernel(const int* __restrict__ idx, const int* __restrict__ n_idx,
                                                          int max_idx, int src_len, int dst_cap, int chunk_size,
                                                          int* __restrict__ pos_out, int* __restrict__ len_out) {
+  __shared__ int wave_sums[4];
   const int n_used = n_idx ? min(max(*n_idx, 0), max_idx) : max_idx;
   const int n_chunks = (src_len + chunk_size - 1) / chunk_size;
-  int off = 0;
-  for (int r = 0; r < n_used; ++r) {
-    const int c = idx[r];
-    const int tokens = chunk_tokens(c, n_chunks, src_len, chunk_size);
+  int base = 0;
+  for (int r0 = 0; r0 < n_used; r0 += blockDim.x) {
+    const int r = r0 + threadIdx.x;
+    int c = -1, tokens = 0;
+    if (r < n_used) {
+      c = idx[r];
+      tokens = chunk_tokens(c, n_chunks, src_len, chunk_size);
+    }
+    int total;
+    const int off = base + block_exclusive_scan(tokens, wave_sums, total);
     if (pos_out)
-      for (int tk = threadIdx.x; tk < tokens; tk += blockDim.x) pos_out[off + tk] = c * chunk_size + tk;
-    off += tokens;
+      for (int tk = 0; tk < tokens; ++tk) pos_out[off + tk] = c * chunk_size + tk;
+    base += total;
   }
   if (pos_out)
-    for (int i = off + threadIdx.x; i < dst_cap; i += blockDim.x) pos_out[i] = -1;
-  if (len_out && threadIdx.x == 0) *len_out = off;
+    for (int i = base + threadIdx.x; i < dst_cap; i += blockDim.x) pos_out[i] = -1;
+  if (len_out && threadIdx.x == 0) *len_out = base;
 }
 
 }  // namespace
 
 hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, float* scores, hipStream_t stream) {
   const int rows = score_row < 0 ? p.T : 1;
-  dim3 grid((p.C + 255) / 256, rows);
+  dim3 grid((p.C + 63) / 64, rows);
   chunk_scores_kernel<<<grid, dim3(256), 0, stream>>>(p, score_row < 0 ? 0 : score_row, scores);
   return hipGetLastError();
 }
 
 hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int32_t* idx_out,
                                 int32_t* n_out, hipStream_t stream) {
-  select_kernel<<<dim3(1), dim3(kSelThreads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
+  // a small input needs only as many waves as it has scores (fewer waves, cheaper barriers)
+  const int threads = n_chunks >= kSelThreads ? kSelThreads : ((n_chunks + 63) / 64) * 64;
+  select_kernel<<<dim3(1), dim3(threads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
   return hipGetLastError();
 }
 

@@ -54,6 +54,22 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
   const int t = m / p.G;
   const int h = g * p.G + m % p.G;
 
+  // The loads of the first 32 split partials are issued before anything else so that
+  // their latency overlaps the tree pass below; they do not depend on it.
+  constexpr int kPre = 32;
+  const int64_t split_stride = static_cast<int64_t>(n_rows) * D;
+  const float* po_row = p.part_o + static_cast<int64_t>(row) * D + lane * E;
+  float2 ml_first = make_float2(-INFINITY, 0.f);
+  if (lane < p.S) ml_first = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(lane) * n_rows + row) * 2);
+  float pre[kPre][E];
+#pragma unroll
+  for (int u = 0; u < kPre; ++u) {
+    if (u < p.S) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) pre[u][e] = po_row[u * split_stride + e];
+    }
+  }
+
   float q[E], o[E];
   load_vec<D, IN_BF16>(p.q, t * p.q_st + h * p.q_sh, lane, q);
 #pragma unroll
@@ -63,25 +79,50 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
   }
   float run_max = -INFINITY, run_sum = 0.f;
 
-  // tree part: node t and its ancestors
+  // tree part: node t and its ancestors.  The parent array (at most 128 entries) is
+  // held two per lane and the chain is walked with cross-lane reads, without touching
+  // memory; the ancestors' K/V rows are then fetched eight at a time so that their
+  // load latencies overlap.  A malformed entry ends the walk (the node is then
+  // treated as a root).
+  const int par_lo = lane < p.T ? p.parent[lane] : -1;
+  const int par_hi = lane + 64 < p.T ? p.parent[lane + 64] : -1;
   int a = t;
   while (a >= 0) {
-    float kv[E];
-    load_vec<D, IN_BF16>(p.kt, g * p.kt_sh + a * p.kt_st, lane, kv);
-    float dot = 0.f;
+    int anc[8];
+    int n_anc = 0;
 #pragma unroll
-    for (int e = 0; e < E; ++e) dot = fmaf(q[e], kv[e], dot);
-    const float s = wave_sum(dot);
-    const float new_max = fmaxf(run_max, s);
-    const float alpha = exp2f(run_max - new_max);
-    const float pr = exp2f(s - new_max);
-    load_vec<D, IN_BF16>(p.vt, g * p.kt_sh + a * p.kt_st, lane, kv);
+    for (int u = 0; u < 8; ++u) {
+      anc[u] = a;
+      if (a >= 0) {
+        ++n_anc;
+        const int par = a < 64 ? __builtin_amdgcn_readlane(par_lo, a) : __builtin_amdgcn_readlane(par_hi, a - 64);
+        a = (par >= a || par < -1) ? -1 : par;
+      }
+    }
+    float kk[8][E], vv[8][E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) o[e] = fmaf(pr, kv[e], o[e] * alpha);
-    run_sum = fmaf(run_sum, alpha, pr);
-    run_max = new_max;
-    const int par = p.parent[a];
-    a = (par >= a || par < -1) ? -1 : par;   // a malformed entry ends the walk (node treated as a root)
+    for (int u = 0; u < 8; ++u) {
+      if (u < n_anc) {
+        load_vec<D, IN_BF16>(p.kt, g * p.kt_sh + anc[u] * p.kt_st, lane, kk[u]);
+        load_vec<D, IN_BF16>(p.vt, g * p.kt_sh + anc[u] * p.kt_st, lane, vv[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (u < n_anc) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) dot = fmaf(q[e], kk[u][e], dot);
+        const float s = wave_sum(dot);
+        const float new_max = fmaxf(run_max, s);
+        const float alpha = exp2f(run_max - new_max);
+        const float pr = exp2f(s - new_max);
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] = fmaf(pr, vv[u][e], o[e] * alpha);
+        run_sum = fmaf(run_sum, alpha, pr);
+        run_max = new_max;
+      }
+    }
   }
 
   // prefix splits.  Lane s first takes (max, sum) of split s (64 splits per round), the
@@ -93,16 +134,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
     const int s_mine = s0 + lane;
     float ms = -INFINITY, ls = 0.f;
     if (s_mine < p.S) {
-      const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(s_mine) * n_rows + row) * 2);
+      const float2 ml = s0 == 0 ? ml_first
+                                : *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(s_mine) * n_rows + row) * 2);
       if (ml.y > 0.f) {              // an empty split contributes nothing
         ms = ml.x;
         ls = ml.y;
       }
     }
-    float round_max = ms;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) round_max = fmaxf(round_max, __shfl_xor(round_max, off, 64));
-    const float new_max = fmaxf(run_max, round_max);
+    const float new_max = fmaxf(run_max, wave_max(ms));
     if (new_max == -INFINITY) continue;          // nothing so far and nothing in this round (wave-uniform)
     const float alpha = exp2f(run_max - new_max);
     const float w = ls > 0.f ? exp2f(ms - new_max) : 0.f;
@@ -111,9 +150,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] *= alpha;
     const int s_end = min(64, p.S - s0);
-    const float* po = p.part_o + (static_cast<int64_t>(s0) * n_rows + row) * D + lane * E;
-    const int64_t split_stride = static_cast<int64_t>(n_rows) * D;
     int s = 0;
+    if (s0 == 0) {                   // the preloaded partials, in split order
+#pragma unroll
+      for (int u = 0; u < kPre; ++u) {
+        if (u < s_end) {
+          const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
+#pragma unroll
+          for (int e = 0; e < E; ++e) o[e] = fmaf(pre[u][e], wu, o[e]);
+        }
+      }
+      s = min(kPre, s_end);
+    }
+    const float* po = po_row + static_cast<int64_t>(s0) * split_stride;
     for (; s + 8 <= s_end; s += 8) {
       float v[8][E];
 #pragma unroll

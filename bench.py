@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+# HBM bytes of one prefix-kernel launch at the default workload (prefix 16384, automatic splits), from the
+# FETCH_SIZE and WRITE_SIZE counter passes summarised in profiles/prefix_rows_kernel_config4_hbm_traffic.md
+# (FETCH_SIZE scaled by 1.9855, WRITE_SIZE by 1.000, the factors a plain copy of known size gives):
+# 70.6 MB fetched + 31.9 MB written.
+MEASURED_TRAFFIC_BYTES = {16384: 70.6e6 + 31.9e6}
 
 
 def parse_args():
@@ -179,13 +184,14 @@ def main():
             "step_mfma_TFLOPs": round(n_layers * flops_per_launch / (step_us * 1e-6) / 1e12, 1),
         },
         "roofline": {
-            "kernel": "prefix_mfma_kernel (split-K prefix pass, one layer per launch)",
+            "kernel": "prefix_rows_kernel<8,false> (split-K prefix pass on the matrix cores, one layer per launch)",
             "bound": "hbm",
             "achieved": round(achieved_gbs, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(L) if (args.num_splits == 0 and n_layers == 32) else None,
+            "algorithmic_bytes": bytes_per_launch,
             "us_per_launch": round(prefix_us, 3),
             "mfma_TFLOPs": round(flops_per_launch / (prefix_us * 1e-6) / 1e12, 1),
             "mfma_frac": round(flops_per_launch / (prefix_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),

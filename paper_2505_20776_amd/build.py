@@ -11,9 +11,11 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libspecext.so")
 # per-source extra flags: both matrix-core kernels are compiled with the matrix-core results in
-# architectural VGPRs (the softmax reads them with vector ALU instructions, which cannot read AGPRs)
+# architectural VGPRs (the softmax reads them with vector ALU instructions, which cannot read AGPRs);
+# the row-split kernel never produces a NaN on its hot path, and saying so spares the max
+# reductions one canonicalising instruction per operand
 EXTRA_FLAGS = {"prefix_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
-               "prefix_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+               "prefix_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"]}
 SOURCES = ["api.hip", "prefix_generic.hip", "prefix_mfma.hip", "prefix_mfma_rows.hip", "tree_merge.hip", "retrieval.hip"]
 
 

@@ -86,8 +86,11 @@ int resolve(const specext_desc* d, AttnParams* p) {
   // Up to 64 query rows per KV head: the key-split kernel (the four waves of a
   // workgroup share the rows and split the keys).  More rows: the row-split kernel
   // (a workgroup owns 128 or 256 rows, so each K/V byte enters one compute unit only).
+  // Their address arithmetic inside a tile and inside Q is 32-bit, hence the stride limits.
   const bool mfma_ok = p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L >= 32 &&
-                       (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX);
+                       (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX) &&
+                       p->kp_sl <= (1 << 24) &&
+                       (p->T - 1) * p->q_st + (p->Hq - 1) * p->q_sh + p->d < (int64_t{1} << 30);
   if (!mfma_ok) {
     p->use_mfma = 0;
     p->rows_per_group = 64;
@@ -97,6 +100,7 @@ int resolve(const specext_desc* d, AttnParams* p) {
   } else {
     p->use_mfma = 2;
     p->rows_per_group = p->M > 128 ? 256 : 128;
+    p->part_bf16 = 1;
   }
   p->score_gran = p->use_mfma ? 32 : p->B;
   p->n_sub = p->want_scores ? (p->L + p->score_gran - 1) / p->score_gran : 0;

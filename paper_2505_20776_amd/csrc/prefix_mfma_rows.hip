@@ -32,17 +32,34 @@ constexpr int kTile = 32;                         // keys per tile
 constexpr int kD = 128;                           // head_dim this kernel is written for
 constexpr int kRowBytes = kD * 2;                 // one bf16 K or V row in LDS
 constexpr int kTileBytes = kTile * kRowBytes;     // 8 KB
-#ifndef SPECEXT_ROWS_RING
-#define SPECEXT_ROWS_RING 4
+#ifndef SPECEXT_ROWS_STAGE_TILES
+#define SPECEXT_ROWS_STAGE_TILES 1
 #endif
-constexpr int kRing = SPECEXT_ROWS_RING;          // tiles per ring (K ring and V ring)
-constexpr int kPatchStride = 64 + 4;              // floats per row of the output staging patch (padded against bank conflicts)
+#ifndef SPECEXT_ROWS_STAGES
+#define SPECEXT_ROWS_STAGES 4
+#endif
+constexpr int kStageTiles = SPECEXT_ROWS_STAGE_TILES;   // tiles between two workgroup barriers
+constexpr int kStages = SPECEXT_ROWS_STAGES;            // stages per ring (>= 2)
+constexpr int kRing = kStageTiles * kStages;            // tiles per ring (K ring and V ring)
 constexpr int kRingBytes = 2 * kRing * kTileBytes;
-constexpr int lds_bytes(int waves) { return kRingBytes > waves * 32 * kPatchStride * 4 ? kRingBytes : waves * 32 * kPatchStride * 4; }
-#ifndef SPECEXT_ROWS_SKEW
-#define SPECEXT_ROWS_SKEW 0
-#endif
-constexpr bool kSkewHalves = SPECEXT_ROWS_SKEW != 0;   // upper half of the waves runs half a tile behind
+// Behind the rings every wave has a private area: first the staging of its 32 query
+// rows (32 x 256 B), at the end the staging of its 32 partial output rows as bf16
+// (rows padded to 264 B so that the 8-byte column writes fall into distinct banks).
+constexpr int kPatchStride = kRowBytes + 8;
+constexpr int kPrivBytes = 32 * kPatchStride;
+constexpr int lds_bytes(int waves) { return kRingBytes + waves * kPrivBytes; }
+static_assert(kStages >= 2 && lds_bytes(8) <= 160 * 1024, "rings and private areas must fit the 160 KB of LDS");
+
+template <int I>
+using ic = std::integral_constant<int, I>;
+// f(ic<0>{}), f(ic<1>{}), ..., f(ic<N-1>{})
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(ic<I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 
 template <int WAVES, bool SCORES>
 __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
@@ -72,9 +89,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   // XOR-swizzled (K: chunk ^ (row & 15), V: chunk ^ ((row & 3) << 2)) so that the
   // operand reads are bank-conflict free; the LDS side of a direct load being fixed,
   // the swizzle is applied to the global address.
-  unsigned char* kring = lds;
-  unsigned char* vring = lds + kRing * kTileBytes;
-  const unsigned kring_lds = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)kring));
+  const unsigned kring_lds = static_cast<unsigned>(reinterpret_cast<uintptr_t>((lds_void*)lds));
   const unsigned vring_lds = kring_lds + kRing * kTileBytes;
   const int ld_row = lane >> 4;          // row within the 4-row block of one load
   const int ld_slot = lane & 15;         // LDS chunk slot this lane fills
@@ -90,9 +105,11 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   // below the tile's own first key belong to the tile before and are masked.
   auto tile_key0 = [&](int t) { return key_lo + t * kTile; };
   auto tile_first_row = [&](int t) { return min(tile_key0(t), key_hi - kTile); };
-  auto issue_tile = [&](int t) {                  // this wave's share of K(t), then of V(t)
+  // this wave's share of K(t), then of V(t), into ring slot SLOT (a compile-time constant,
+  // so that every LDS address below is a loop-invariant register plus an immediate)
+  auto issue_tile = [&](auto slot_c, int t) {
+    constexpr unsigned slot = decltype(slot_c)::value * kTileBytes;
     const int64_t off = static_cast<int64_t>(tile_first_row(t)) * row_bytes;
-    const unsigned slot = (t % kRing) * kTileBytes;
 #pragma unroll
     for (int u = 0; u < kLoadsPerWave; ++u) {
       const int blk = kLoadsPerWave * wave + u;
@@ -104,42 +121,69 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       load_to_lds_16(vring_lds + slot + blk * 1024, v_voff, vbase + off + blk * 4 * row_bytes);
     }
   };
+  // stage s = tiles [s * kStageTiles, (s + 1) * kStageTiles) of the split, cut at n; it
+  // lives in ring stage s % kStages
+  const int n_stages = (n + kStageTiles - 1) / kStageTiles;
+  auto issue_stage = [&](auto ring_stage_c, int s) {
+    constexpr int ring_stage = decltype(ring_stage_c)::value;
+    static_for<0, kStageTiles>([&](auto i_c) {
+      constexpr int i = decltype(i_c)::value;
+      const int t = s * kStageTiles + i;
+      if (t < n) issue_tile(ic<ring_stage * kStageTiles + i>{}, t);
+    });
+  };
+  // load instructions of this wave that are younger than those of stage s, once the
+  // stages up to s + kStages - 2 have been requested
+  constexpr int kLoadsPerTile = 2 * kLoadsPerWave;
+  auto younger_than_stage = [&](int s) {
+    return kLoadsPerTile * (min((s + kStages - 1) * kStageTiles, n) - min((s + 1) * kStageTiles, n));
+  };
 
-  // prologue: the first kRing-2 tiles are requested, and in between the queries
-  // (B operand of S^T: lane = row c32, 8 consecutive d per k-step) with plain loads
-  // in inline assembly, so that waiting for them does not drain the tile prefetch
-  issue_tile(0);
-  bf16x8 qf[8];
+  // prologue: the first kStages-1 stages are requested, and after the first of them
+  // the queries (B operand of S^T: lane = row c32, 8 consecutive d per k-step) with
+  // plain loads in inline assembly, so that waiting for them does not drain the prefetch
+  issue_stage(ic<0>{}, 0);
+  const unsigned priv_lds = kring_lds + kRingBytes + wave * kPrivBytes;
   {
-    const int mq = min(m, p.M - 1);               // padding rows repeat the last real row (never stored)
-    const uint16_t* qp =
-        static_cast<const uint16_t*>(p.q) + (mq / p.G) * p.q_st + (g * p.G + mq % p.G) * p.q_sh + 8 * hf;
+    // load u brings rows 4u..4u+3 of the wave (1 KB); the lane that fills LDS chunk
+    // slot `ld_slot` of row r fetches chunk ld_slot ^ (r & 15) of that query row (the K
+    // swizzle, so that the fragment reads below use the K read offsets)
+    const float inv_g = 1.0f / static_cast<float>(p.G);
+    const unsigned char* qbase = static_cast<const unsigned char*>(p.q);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qf[ks]) : "v"(qp + 16 * ks) : "memory");
-  }
-  int younger = 0;                                // load instructions issued after the query loads
-#pragma unroll
-  for (int t = 1; t < kRing - 2; ++t) {
-    if (t < n) {
-      issue_tile(t);
-      younger += 2 * kLoadsPerWave;
+    for (int u = 0; u < 8; ++u) {
+      const int r = 4 * u + ld_row;
+      const int mq = min(row0 + r, p.M - 1);               // padding rows repeat the last real row (never stored)
+      const int tq = static_cast<int>((static_cast<float>(mq) + 0.5f) * inv_g);   // mq / G, exact for mq < 2^20
+      const int hq = g * p.G + (mq - tq * p.G);
+      const unsigned voff = static_cast<unsigned>((tq * p.q_st + hq * p.q_sh) * 2) + ((ld_slot ^ (r & 15)) << 4);
+      load_to_lds_16(priv_lds + u * 1024, voff, qbase);
     }
   }
-  wait_vmcnt_even(younger);                       // tile 0 (this wave's share) and the queries have landed
-  asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]),
-                    "+v"(qf[7]) :: "memory");     // no use of the fragments may move above the wait
+  static_for<1, kStages - 1>([&](auto u_c) {
+    constexpr int u = decltype(u_c)::value;
+    if (u < n_stages) issue_stage(ic<u>{}, u);
+  });
 
   // K operand read: row c32, chunk (2*ks + hf) ^ (c32 & 15)
-  const int k_rd_base = c32 * kRowBytes + ((hf ^ (c32 & 1)) << 4);
-  const int k_rd_xor = c32 & 14;
+  unsigned k_rd[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_rd[ks] = c32 * kRowBytes + ((((2 * ks) ^ (c32 & 14)) | (hf ^ (c32 & 1))) << 4);
   // V transpose read: a group of 16 lanes reads 4 keys x 16 dcols
   const int li = lane & 15;
   const int grp_col = (lane >> 4) & 1;                  // which 16-column half of the 32-dcol block
   const int v_key_in = 4 * hf + (li >> 2);              // + 16 * jj (+ 8)
-  const int v_rd_base = v_key_in * kRowBytes + ((2 * grp_col + ((li & 3) >> 1)) << 4) + ((li & 1) << 3);
   const int v_q4 = li >> 2;                             // (row & 3) of the row this lane addresses
+  unsigned v_rd[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+    v_rd[db] = kRing * kTileBytes + v_key_in * kRowBytes + ((db ^ v_q4) << 6) + ((2 * grp_col + ((li & 3) >> 1)) << 4) +
+               ((li & 1) << 3);
 
+  // queries: B operand of S^T (lane = row c32, 8 consecutive d per k-step), read from
+  // the private area once the first wait below has passed
+  bf16x8 qf[8];
+  unsigned char* priv = lds + kRingBytes + wave * kPrivBytes;
   floatx16 acc_o[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
@@ -151,36 +195,20 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const float lazy_raw = kLazyLog2 / c;      // the lazy margin in raw-logit units
   const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  // Each wave's loads form the sequence K0 V0 K1 V1 ... (kLoadsPerWave instructions per
-  // entry).  After barrier j every wave is done with tile j-2 (see the skew below), so
-  // tile j-2+kRing is requested into that slot; before iteration j the tiles up to
-  // min(j + kRing - 3, n - 1) have been requested and tile j is needed.
-  auto top = [&](int j) {
-    const int younger_tiles = min(j + kRing - 3, n - 1) - j;
-    if (younger_tiles == kRing - 3) {
-      asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kLoadsPerWave * (kRing - 3)) : "memory");
-    } else {
-      wait_vmcnt_even(2 * kLoadsPerWave * younger_tiles);
-    }
-    lds_barrier();            // every share of tile j has landed
-    if (j - 2 + kRing < n) issue_tile(j - 2 + kRing);
-  };
-
-  floatx16 s;                  // logits, then probabilities, of the tile in flight
-  bf16x8 vf[4][2];             // its V^T fragments
-  // first half of a tile: logits, V^T fragments requested, shifted-tile mask
-  auto logits = [&](int j) {
-    const unsigned char* kst = kring + (j % kRing) * kTileBytes + k_rd_base;
-    s = zero16;
+  // One tile: logits, online softmax (one query row per lane pair, the reference moves
+  // lazily), O^T += V^T P^T.  SLOT is the tile's ring slot.
+  auto tile = [&](auto slot_c, int j) {
+    constexpr int slot = decltype(slot_c)::value * kTileBytes;
+    floatx16 s = zero16;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      const uintx4 kw = *reinterpret_cast<const uintx4*>(kst + (((2 * ks) ^ k_rd_xor) << 4));
+      const uintx4 kw = *reinterpret_cast<const uintx4*>(lds + k_rd[ks] + slot);
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[ks], s, 0, 0, 0);
     }
-    const unsigned char* vst = vring + (j % kRing) * kTileBytes + v_rd_base;
+    bf16x8 vf[4][2];             // the tile's V^T fragments
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
-      const unsigned char* col = vst + ((db ^ v_q4) << 6);
+      const unsigned char* col = lds + v_rd[db] + slot;
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(col + (16 * jj) * kRowBytes));
@@ -198,10 +226,6 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
         if (key < key0) s[r] = -INFINITY;
       }
     }
-  };
-  // second half: online softmax (one query row per lane pair, the reference moves
-  // lazily), then O^T += V^T P^T
-  auto softmax_pv = [&](int j) {
     float mx = fmaxf(s[0], s[1]);
 #pragma unroll
     for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[r], s[r + 1]));
@@ -227,7 +251,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     if (SCORES) {
       const float tot = part + __shfl_xor(part, 32, 64);
       if (hf == 0 && m < p.M) {
-        float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + tile_key0(j) / kTile) * p.M + m) * 2;
+        float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + key0 / kTile) * p.M + m) * 2;
         *reinterpret_cast<floatx2*>(cp) = floatx2{tot, mc};
       }
     }
@@ -240,57 +264,68 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     }
   };
 
-  // The waves of the upper half of the workgroup run half a tile behind the lower
-  // half: between two barriers the lower half does logits(j) then softmax_pv(j), the
-  // upper half softmax_pv(j-1) then logits(j).  The two waves that share a SIMD (w and
-  // w + WAVES/2) are thus in different phases, and one's matrix work overlaps the
-  // other's vector work.  Both halves pass the same n barriers.
-  if (!kSkewHalves || wave < WAVES / 2) {
-    for (int j = 0; j < n; ++j) {
-      top(j);
-      logits(j);
-      softmax_pv(j);
-    }
-  } else {
-    top(0);
-    logits(0);
-    for (int j = 1; j < n; ++j) {
-      top(j);
-      softmax_pv(j - 1);
-      logits(j);
-    }
-    softmax_pv(n - 1);
+  // Each wave's loads form the sequence (K, V of tile 0), (K, V of tile 1), ...  Before
+  // stage s is read every wave waits for its own share of it and meets the others at a
+  // barrier; behind that barrier every wave has also left stage s-1, whose ring stage
+  // takes the loads of stage s + kStages - 1.  Between two barriers the waves run free,
+  // so the two waves of a SIMD drift into opposite phases (one in its matrix
+  // products while the other does its softmax arithmetic).
+  for (int s0 = 0; s0 < n_stages; s0 += kStages) {
+    static_for<0, kStages>([&](auto u_c) {
+      constexpr int u = decltype(u_c)::value;
+      const int s = s0 + u;
+      if (s < n_stages) {
+        if (s == 0) {
+          wait_vmcnt_even(younger_than_stage(0));        // also covers the wave's own queries
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks)
+            qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(priv + k_rd[ks]));
+        } else if ((s + kStages - 1) * kStageTiles <= n) {
+          asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kLoadsPerTile * kStageTiles * (kStages - 2)) : "memory");
+        } else {
+          wait_vmcnt_even(younger_than_stage(s));
+        }
+        lds_barrier();
+        if (s + kStages - 1 < n_stages) issue_stage(ic<(u + kStages - 1) % kStages>{}, s + kStages - 1);
+        static_for<0, kStageTiles>([&](auto i_c) {
+          constexpr int i = decltype(i_c)::value;
+          const int j = s * kStageTiles + i;
+          if (j < n) tile(ic<u * kStageTiles + i>{}, j);
+        });
+      }
+    });
   }
 
-  // ---- partial results of this split: unnormalised O, reference (base-2 units) and row sum.
-  // O^T sits in registers with a lane owning one row; it goes through a wave-private
-  // LDS patch (two halves of 64 columns) so that the global stores are 256-byte runs.
+  // ---- partial results of this split: unnormalised O as bf16, reference (base-2 units)
+  // and row sum in fp32.  O^T sits in registers with a lane owning one row; it goes
+  // through the wave's private LDS area so that the global stores are whole 256-byte rows.
   const float l_tot = run_sum + __shfl_xor(run_sum, 32, 64);
-  lds_barrier();                                   // every wave is done with the tile rings
-  float* patch = reinterpret_cast<float*>(lds) + wave * (32 * kPatchStride);
   const int64_t slot0 = static_cast<int64_t>(split) * p.Hq * p.T + g * p.M + row0;     // slot of the wave's first row
   const int rows_here = min(32, p.M - row0);       // <= 0 for a wave of padding rows only
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
+  for (int db = 0; db < 4; ++db) {
 #pragma unroll
-    for (int d2 = 0; d2 < 2; ++d2) {
-      const int db = 2 * half + d2;
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-        *reinterpret_cast<floatx4*>(patch + c32 * kPatchStride + 32 * d2 + 8 * r4 + 4 * hf) =
-            floatx4{acc_o[db][4 * r4], acc_o[db][4 * r4 + 1], acc_o[db][4 * r4 + 2], acc_o[db][4 * r4 + 3]};
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const floatx2 lo = {acc_o[db][4 * r4], acc_o[db][4 * r4 + 1]};
+      const floatx2 hi = {acc_o[db][4 * r4 + 2], acc_o[db][4 * r4 + 3]};
+      const bf16x2 blo = __builtin_convertvector(lo, bf16x2);
+      const bf16x2 bhi = __builtin_convertvector(hi, bf16x2);
+      uintx2 w;
+      w[0] = __builtin_bit_cast(uint32_t, blo);
+      w[1] = __builtin_bit_cast(uint32_t, bhi);
+      *reinterpret_cast<uintx2*>(priv + c32 * kPatchStride + (32 * db + 8 * r4 + 4 * hf) * 2) = w;
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_wave_barrier();
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+  uint16_t* part_h = reinterpret_cast<uint16_t*>(p.part_o);
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int row = 4 * it + (lane >> 4);
-      const floatx4 v = *reinterpret_cast<const floatx4*>(patch + row * kPatchStride + 4 * (lane & 15));
-      if (row < rows_here)
-        *reinterpret_cast<floatx4*>(p.part_o + (slot0 + row) * kD + 64 * half + 4 * (lane & 15)) = v;
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_wave_barrier();
+  for (int it = 0; it < 8; ++it) {
+    const int row = 4 * it + (lane >> 4);
+    const uintx2* src = reinterpret_cast<const uintx2*>(priv + row * kPatchStride + 16 * (lane & 15));
+    const uintx2 a = src[0], b = src[1];
+    if (row < rows_here)
+      *reinterpret_cast<uintx4*>(part_h + (slot0 + row) * kD + 8 * (lane & 15)) = uintx4{a[0], a[1], b[0], b[1]};
   }
   if (hf == 0 && m < p.M) {
     p.part_ml[(slot0 + c32) * 2] = ref * c;

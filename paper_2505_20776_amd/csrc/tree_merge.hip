@@ -32,9 +32,12 @@ __device__ __forceinline__ void load_vec(const void* base, int64_t off, int lane
   }
 }
 
-template <int D, bool IN_BF16>
+// PART_BF16: the prefix kernel wrote its partial outputs as bf16 (row-split matrix-core
+// kernel, D = 128) instead of fp32; a lane's two values are then one 32-bit word.
+template <int D, bool IN_BF16, bool PART_BF16>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnParams p) {
   constexpr int E = D / 64;
+  static_assert(!PART_BF16 || E == 2, "bf16 partials are written for head_dim 128 only");
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);   // rid
   const int n_rows = p.Hq * p.T;
@@ -59,15 +62,32 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
   constexpr int kPre = 32;
   const int64_t split_stride = static_cast<int64_t>(n_rows) * D;
   const float* po_row = p.part_o + static_cast<int64_t>(row) * D + lane * E;
+  const uint32_t* po_row_h = reinterpret_cast<const uint32_t*>(p.part_o) + static_cast<int64_t>(row) * (D / 2) + lane;
+  constexpr int PE = PART_BF16 ? 1 : E;          // 32-bit words a lane holds per partial
+  // raw words of split s (fetch) and their fp32 values (decode)
+  auto fetch = [&](int64_t s, uint32_t (&w)[PE]) {
+    if (PART_BF16) {
+      w[0] = po_row_h[s * (split_stride / 2)];
+    } else {
+#pragma unroll
+      for (int e = 0; e < PE; ++e) w[e] = __float_as_uint(po_row[s * split_stride + e]);
+    }
+  };
+  auto decode = [&](const uint32_t (&w)[PE], float (&v)[E]) {
+    if (PART_BF16) {
+      v[0] = __uint_as_float(w[0] << 16);
+      v[E - 1] = __uint_as_float(w[0] & 0xffff0000u);
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) v[e] = __uint_as_float(w[e]);
+    }
+  };
   float2 ml_first = make_float2(-INFINITY, 0.f);
   if (lane < p.S) ml_first = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(lane) * n_rows + row) * 2);
-  float pre[kPre][E];
+  uint32_t pre[kPre][PE];
 #pragma unroll
   for (int u = 0; u < kPre; ++u) {
-    if (u < p.S) {
-#pragma unroll
-      for (int e = 0; e < E; ++e) pre[u][e] = po_row[u * split_stride + e];
-    }
+    if (u < p.S) fetch(u, pre[u]);
   }
 
   float q[E], o[E];
@@ -156,30 +176,35 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
       for (int u = 0; u < kPre; ++u) {
         if (u < s_end) {
           const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
+          float v[E];
+          decode(pre[u], v);
 #pragma unroll
-          for (int e = 0; e < E; ++e) o[e] = fmaf(pre[u][e], wu, o[e]);
+          for (int e = 0; e < E; ++e) o[e] = fmaf(v[e], wu, o[e]);
         }
       }
       s = min(kPre, s_end);
     }
-    const float* po = po_row + static_cast<int64_t>(s0) * split_stride;
     for (; s + 8 <= s_end; s += 8) {
-      float v[8][E];
+      uint32_t raw[8][PE];
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
-#pragma unroll
-        for (int e = 0; e < E; ++e) v[u][e] = po[(s + u) * split_stride + e];
+      for (int u = 0; u < 8; ++u) fetch(s0 + s + u, raw[u]);
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), s + u));
+        float v[E];
+        decode(raw[u], v);
 #pragma unroll
-        for (int e = 0; e < E; ++e) o[e] = fmaf(v[u][e], wu, o[e]);
+        for (int e = 0; e < E; ++e) o[e] = fmaf(v[e], wu, o[e]);
       }
     }
     for (; s < s_end; ++s) {
       const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), s));
+      uint32_t raw[PE];
+      fetch(s0 + s, raw);
+      float v[E];
+      decode(raw, v);
 #pragma unroll
-      for (int e = 0; e < E; ++e) o[e] = fmaf(po[s * split_stride + e], wu, o[e]);
+      for (int e = 0; e < E; ++e) o[e] = fmaf(v[e], wu, o[e]);
     }
   }
 
@@ -213,12 +238,14 @@ hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream) {
   dim3 grid((n_rows + kWavesPerBlock - 1) / kWavesPerBlock);
   dim3 block(kWavesPerBlock * 64);
   const bool bf16 = p.in_dtype == SPECEXT_BF16;
+  if (p.part_bf16 && !(p.d == 128 && bf16)) return hipErrorInvalidValue;
   if (p.d == 128) {
-    if (bf16) tree_merge_kernel<128, true><<<grid, block, 0, stream>>>(p);
-    else tree_merge_kernel<128, false><<<grid, block, 0, stream>>>(p);
+    if (p.part_bf16) tree_merge_kernel<128, true, true><<<grid, block, 0, stream>>>(p);
+    else if (bf16) tree_merge_kernel<128, true, false><<<grid, block, 0, stream>>>(p);
+    else tree_merge_kernel<128, false, false><<<grid, block, 0, stream>>>(p);
   } else {
-    if (bf16) tree_merge_kernel<64, true><<<grid, block, 0, stream>>>(p);
-    else tree_merge_kernel<64, false><<<grid, block, 0, stream>>>(p);
+    if (bf16) tree_merge_kernel<64, true, false><<<grid, block, 0, stream>>>(p);
+    else tree_merge_kernel<64, false, false><<<grid, block, 0, stream>>>(p);
   }
   return hipGetLastError();
 }

@@ -100,7 +100,7 @@ int resolve(const specext_desc* d, AttnParams* p) {
   } else {
     p->use_mfma = 2;
     p->rows_per_group = p->M > 128 ? 256 : 128;
-    p->part_bf16 = 1;
+    p->part_f16 = 1;
   }
   p->score_gran = p->use_mfma ? 32 : p->B;
   p->n_sub = p->want_scores ? (p->L + p->score_gran - 1) / p->score_gran : 0;

@@ -39,7 +39,7 @@ struct AttnParams {
   int32_t score_gran, n_sub;      // keys per score block (32 on the MFMA path, else B) and their count
   int32_t use_mfma;               // 0 vector-ALU kernel, 1 matrix-core key-split kernel, 2 matrix-core row-split kernel
   int32_t rows_per_group;         // query rows of one KV head that one workgroup covers
-  int32_t part_bf16;              // 1: part_o holds bf16 [S][rows][d] (row-split kernel), 0: fp32
+  int32_t part_f16;               // 1: part_o holds O/l as fp16 [S][rows][d] (row-split kernel), 0: unnormalised O as fp32
   int32_t in_dtype, out_dtype;
   float scale_log2;
   int64_t q_st, q_sh, kp_sh, kp_sl, kt_sh, kt_st, o_st, o_sh;
@@ -84,6 +84,24 @@ __device__ __forceinline__ float wave_sum(float v) {
   const int b = __float_as_int(v);
   return (__int_as_float(__builtin_amdgcn_readlane(b, 0)) + __int_as_float(__builtin_amdgcn_readlane(b, 16))) +
          (__int_as_float(__builtin_amdgcn_readlane(b, 32)) + __int_as_float(__builtin_amdgcn_readlane(b, 48)));
+}
+
+// the same two reductions over each aligned group of 16 lanes (one DPP row); every
+// lane of a group receives its group's result
+__device__ __forceinline__ float row16_sum(float v) {
+  v += SPECEXT_DPP(v, 0xB1);
+  v += SPECEXT_DPP(v, 0x4E);
+  v += SPECEXT_DPP(v, 0x141);
+  v += SPECEXT_DPP(v, 0x140);
+  return v;
+}
+
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, SPECEXT_DPP(v, 0xB1));
+  v = fmaxf(v, SPECEXT_DPP(v, 0x4E));
+  v = fmaxf(v, SPECEXT_DPP(v, 0x141));
+  v = fmaxf(v, SPECEXT_DPP(v, 0x140));
+  return v;
 }
 
 __device__ __forceinline__ float wave_max(float v) {

@@ -14,6 +14,7 @@ typedef __attribute__((ext_vector_type(4))) short shortx4;
 typedef __attribute__((ext_vector_type(8))) short shortx8;
 typedef __attribute__((ext_vector_type(4))) uint32_t uintx4;
 typedef __attribute__((ext_vector_type(2))) uint32_t uintx2;
+typedef __attribute__((ext_vector_type(2))) _Float16 halfx2;
 typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
 typedef __attribute__((address_space(3))) void lds_void;
 
@@ -22,6 +23,18 @@ typedef __attribute__((address_space(3))) void lds_void;
 constexpr float kLazyLog2 = 10.f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Lanes l and l+32 exchange through v_permlane32_swap (no LDS access, so no wait on
+// the LDS queue): of the two results one holds the lower half's values in both halves,
+// the other the upper half's.
+__device__ __forceinline__ float halves_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float halves_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 // 8 consecutive accumulator values -> 8 bf16 (round to nearest even)
 __device__ __forceinline__ bf16x8 pack8(const floatx16& v, int first) {

@@ -43,7 +43,7 @@ constexpr int kStages = SPECEXT_ROWS_STAGES;            // stages per ring (>= 2
 constexpr int kRing = kStageTiles * kStages;            // tiles per ring (K ring and V ring)
 constexpr int kRingBytes = 2 * kRing * kTileBytes;
 // Behind the rings every wave has a private area: first the staging of its 32 query
-// rows (32 x 256 B), at the end the staging of its 32 partial output rows as bf16
+// rows (32 x 256 B), at the end the staging of its 32 partial output rows as fp16
 // (rows padded to 264 B so that the 8-byte column writes fall into distinct banks).
 constexpr int kPatchStride = kRowBytes + 8;
 constexpr int kPrivBytes = 32 * kPatchStride;
@@ -195,6 +195,11 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const float lazy_raw = kLazyLog2 / c;      // the lazy margin in raw-logit units
   const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+  // where this lane's (sum, reference) pair of tile j goes: score_base + j * score_step
+  float* score_base = nullptr;
+  const int score_step = p.M * 2;
+  if (SCORES) score_base = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + key_lo / kTile) * p.M + min(m, p.M - 1)) * 2;
+
   // One tile: logits, online softmax (one query row per lane pair, the reference moves
   // lazily), O^T += V^T P^T.  SLOT is the tile's ring slot.
   auto tile = [&](auto slot_c, int j) {
@@ -230,7 +235,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
 #pragma unroll
     for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[r], s[r + 1]));
     if (__any(mx > ref + lazy_raw)) {     // some row of this wave outgrew its reference: move every reference up
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = halves_max(mx);
       const float new_ref = fmaxf(ref, mx);
       const float alpha = fast_exp2((ref - new_ref) * c);     // 0 on the first tile
       ref = new_ref;
@@ -249,10 +254,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     }
     run_sum += part;
     if (SCORES) {
-      const float tot = part + __shfl_xor(part, 32, 64);
+      const float tot = halves_sum(part);
       if (hf == 0 && m < p.M) {
-        float* cp = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + key0 / kTile) * p.M + m) * 2;
-        *reinterpret_cast<floatx2*>(cp) = floatx2{tot, mc};
+        *reinterpret_cast<floatx2*>(score_base + j * score_step) = floatx2{tot, mc};
       }
     }
     const bf16x8 pf0 = pack8(s, 0);
@@ -296,23 +300,26 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     });
   }
 
-  // ---- partial results of this split: unnormalised O as bf16, reference (base-2 units)
-  // and row sum in fp32.  O^T sits in registers with a lane owning one row; it goes
-  // through the wave's private LDS area so that the global stores are whole 256-byte rows.
-  const float l_tot = run_sum + __shfl_xor(run_sum, 32, 64);
+  // ---- partial results of this split: O divided by its row sum, as fp16 (clamped to the
+  // fp16 range: a convex combination of V rows, so only |V| beyond 65504 would clip),
+  // with the reference (base-2 units) and the row sum in fp32.  O^T sits in registers
+  // with a lane owning one row; it goes through the wave's private LDS area so that the
+  // global stores are whole 256-byte rows.
+  const float l_tot = halves_sum(run_sum);
+  const float inv_l = 1.0f / l_tot;
+  auto to_half2 = [&](float x, float y) {
+    const floatx2 f = {__builtin_amdgcn_fmed3f(x * inv_l, -65504.f, 65504.f), __builtin_amdgcn_fmed3f(y * inv_l, -65504.f, 65504.f)};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, halfx2));
+  };
   const int64_t slot0 = static_cast<int64_t>(split) * p.Hq * p.T + g * p.M + row0;     // slot of the wave's first row
   const int rows_here = min(32, p.M - row0);       // <= 0 for a wave of padding rows only
 #pragma unroll
   for (int db = 0; db < 4; ++db) {
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
-      const floatx2 lo = {acc_o[db][4 * r4], acc_o[db][4 * r4 + 1]};
-      const floatx2 hi = {acc_o[db][4 * r4 + 2], acc_o[db][4 * r4 + 3]};
-      const bf16x2 blo = __builtin_convertvector(lo, bf16x2);
-      const bf16x2 bhi = __builtin_convertvector(hi, bf16x2);
       uintx2 w;
-      w[0] = __builtin_bit_cast(uint32_t, blo);
-      w[1] = __builtin_bit_cast(uint32_t, bhi);
+      w[0] = to_half2(acc_o[db][4 * r4], acc_o[db][4 * r4 + 1]);
+      w[1] = to_half2(acc_o[db][4 * r4 + 2], acc_o[db][4 * r4 + 3]);
       *reinterpret_cast<uintx2*>(priv + c32 * kPatchStride + (32 * db + 8 * r4 + 4 * hf) * 2) = w;
     }
   }

@@ -1,97 +1,218 @@
 // Tree pass and log-sum-exp merge of Hybrid Tree Attention (SpecExtend Sec. 3.1).
 //
-// One wavefront per query row (tree node t of query head h).  The lanes hold
-// the head dimension.  The wave first walks the node's ancestor chain through
-// parent[] (the tree mask lets a node see itself and its ancestors only) with
-// an online softmax, then folds in the prefix splits in split order, each
-// weighted by exp2(max_split - max_total).  The merge is a fixed-order fp32
-// reduction: no atomics, bit-reproducible from run to run.
+// Sixteen lanes per query row (tree node t of query head h), four rows per
+// wavefront; a lane holds D/16 consecutive elements of the head dimension.  Each
+// group of 16 lanes first walks its node's ancestor chain through parent[] (the
+// tree mask lets a node see itself and its ancestors only) with an online
+// softmax, then folds in the prefix splits in split order, each weighted by
+// exp2(max_split - max_total).  The merge is a fixed-order fp32 reduction: no
+// atomics, bit-reproducible from run to run.
+//
+// The prefix kernels leave one partial per (split, row): (max, sum) in base-2 units
+// plus either the unnormalised output in fp32, or (row-split matrix-core kernel)
+// the output already divided by its sum, in fp16.
 #include "common.h"
 
 namespace specext {
 namespace {
 
-constexpr int kWavesPerBlock = 4;
+constexpr int kWavesPerBlock = 1;             // small workgroups: the rows spread over every compute unit
+constexpr int kRowsPerWave = 4;
+constexpr int kRowsPerBlock = kWavesPerBlock * kRowsPerWave;
 
-template <int D, bool IN_BF16>
-__device__ __forceinline__ void load_vec(const void* base, int64_t off, int lane, float (&v)[D / 64]) {
-  constexpr int E = D / 64;
-  if (IN_BF16) {
-    const uint16_t* b = static_cast<const uint16_t*>(base) + off + lane * E;
-    if (E == 2) {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(b);
-      v[0] = __uint_as_float(w << 16);
-      v[E - 1] = __uint_as_float(w & 0xffff0000u);
+typedef __attribute__((ext_vector_type(2))) _Float16 halfx2;
+
+// N consecutive values starting at element `off` of a bf16 or fp32 array, as fp32
+template <int N, bool BF16>
+__device__ __forceinline__ void load_row_part(const void* base, int64_t off, float (&v)[N]) {
+  if (BF16) {
+    const uint32_t* b = reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(base) + off);
+    uint32_t w[N / 2];
+    if constexpr (N == 8) {
+      const uint4 x = *reinterpret_cast<const uint4*>(b);
+      w[0] = x.x; w[1] = x.y; w[N / 2 - 2] = x.z; w[N / 2 - 1] = x.w;
     } else {
-      v[0] = bf16_bits_to_float(b[0]);
+      const uint2 x = *reinterpret_cast<const uint2*>(b);
+      w[0] = x.x; w[1] = x.y;
+    }
+#pragma unroll
+    for (int e = 0; e < N / 2; ++e) {
+      v[2 * e] = __uint_as_float(w[e] << 16);
+      v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
     }
   } else {
-    const float* b = static_cast<const float*>(base) + off + lane * E;
+    const float4* b = reinterpret_cast<const float4*>(static_cast<const float*>(base) + off);
 #pragma unroll
-    for (int e = 0; e < E; ++e) v[e] = b[e];
+    for (int e = 0; e < N / 4; ++e) {
+      const float4 x = b[e];
+      v[4 * e] = x.x; v[4 * e + 1] = x.y; v[4 * e + 2] = x.z; v[4 * e + 3] = x.w;
+    }
   }
 }
 
-// PART_BF16: the prefix kernel wrote its partial outputs as bf16 (row-split matrix-core
-// kernel, D = 128) instead of fp32; a lane's two values are then one 32-bit word.
-template <int D, bool IN_BF16, bool PART_BF16>
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// value of `v` in lane `src` (any lane of the wave) for every lane
+__device__ __forceinline__ float lane_read(float v, int src) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(src << 2, __float_as_int(v)));
+}
+
+template <int D, bool IN_BF16, bool PART_F16>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnParams p) {
-  constexpr int E = D / 64;
-  static_assert(!PART_BF16 || E == 2, "bf16 partials are written for head_dim 128 only");
+  constexpr int E = D / 16;                      // elements per lane: 8 or 4
+  static_assert(!PART_F16 || D == 128, "fp16 partials are written for head_dim 128 only");
+  __shared__ int parent_lds[SPECEXT_MAX_TREE];
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);   // rid
+  const int li = lane & 15;                      // position inside the row's group
+  const int grp0 = lane & 48;                    // first lane of the group
   const int n_rows = p.Hq * p.T;
-  if (blockIdx.x == 0 && threadIdx.x < 64) {
-    // single writer of the status word: 1 if any parent index is not a topological one
-    bool bad = false;
-    for (int i = lane; i < p.T; i += 64) {
-      const int par = p.parent[i];
-      bad |= (par >= i) || (par < -1);
-    }
-    const bool any_bad = __any(bad);
-    if (lane == 0) *p.status = any_bad ? 1 : 0;
+  // parent[] first (at most two entries per thread): everything that follows waits for it
+  constexpr int kThreads = kWavesPerBlock * 64;
+  constexpr int kParPerThread = (SPECEXT_MAX_TREE + kThreads - 1) / kThreads;
+  int par_reg[kParPerThread];
+#pragma unroll
+  for (int i = 0; i < kParPerThread; ++i) {
+    const int idx = threadIdx.x + i * kThreads;
+    par_reg[i] = idx < p.T ? p.parent[idx] : -1;
   }
-  if (row >= n_rows) return;
+  const int row_raw = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 4);
+  const bool live = row_raw < n_rows;
+  const int row = live ? row_raw : n_rows - 1;   // groups past the end repeat the last row and store nothing
   const int g = row / p.M;
   const int m = row - g * p.M;
   const int t = m / p.G;
   const int h = g * p.G + m % p.G;
 
-  // The loads of the first 32 split partials are issued before anything else so that
-  // their latency overlaps the tree pass below; they do not depend on it.
-  constexpr int kPre = 32;
+  // Everything below is ordered so that no wait is longer than it must be: loads return in
+  // issue order, so the parent array (first, above) is followed by the query, the
+  // (max, sum) pairs and the first kPre split partials, which depend on nothing, and only
+  // then, once the ancestor chain is known, by the tree K/V rows.  The arithmetic takes
+  // the same order: prefix splits first (in split order), tree part last.
+  float q[E], o[E];
+  load_row_part<E, IN_BF16>(p.q, t * p.q_st + h * p.q_sh + li * E, q);
+  constexpr int kRound = 16;                     // splits whose (max, sum) one group holds, one per lane
+  constexpr int kPre = PART_F16 ? 32 : 16;       // partials requested up front
+  constexpr int PW = PART_F16 ? E / 2 : E;       // 32-bit words a lane holds per partial
   const int64_t split_stride = static_cast<int64_t>(n_rows) * D;
-  const float* po_row = p.part_o + static_cast<int64_t>(row) * D + lane * E;
-  const uint32_t* po_row_h = reinterpret_cast<const uint32_t*>(p.part_o) + static_cast<int64_t>(row) * (D / 2) + lane;
-  constexpr int PE = PART_BF16 ? 1 : E;          // 32-bit words a lane holds per partial
-  // raw words of split s (fetch) and their fp32 values (decode)
-  auto fetch = [&](int64_t s, uint32_t (&w)[PE]) {
-    if (PART_BF16) {
-      w[0] = po_row_h[s * (split_stride / 2)];
+  const uint32_t* po_words = PART_F16 ? reinterpret_cast<const uint32_t*>(p.part_o) + (static_cast<int64_t>(row) * D + li * E) / 2
+                                      : reinterpret_cast<const uint32_t*>(p.part_o) + static_cast<int64_t>(row) * D + li * E;
+  const int64_t split_words = PART_F16 ? split_stride / 2 : split_stride;
+  auto fetch_from = [&](const uint32_t* src, uint32_t (&w)[PW]) {
+    if constexpr (PW == 4) {
+      const uint4 x = *reinterpret_cast<const uint4*>(src);
+      w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
+    } else if constexpr (PW == 8) {
+      const uint4 x = *reinterpret_cast<const uint4*>(src), y = *reinterpret_cast<const uint4*>(src + 4);
+      w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
+      w[4] = y.x; w[5] = y.y; w[6] = y.z; w[7] = y.w;
     } else {
-#pragma unroll
-      for (int e = 0; e < PE; ++e) w[e] = __float_as_uint(po_row[s * split_stride + e]);
+      const uint2 x = *reinterpret_cast<const uint2*>(src);
+      w[0] = x.x; w[1] = x.y;
     }
   };
-  auto decode = [&](const uint32_t (&w)[PE], float (&v)[E]) {
-    if (PART_BF16) {
-      v[0] = __uint_as_float(w[0] << 16);
-      v[E - 1] = __uint_as_float(w[0] & 0xffff0000u);
+  auto fetch = [&](int s, uint32_t (&w)[PW]) { fetch_from(po_words + s * split_words, w); };
+  auto accumulate = [&](const uint32_t (&w)[PW], float weight) {
+    if constexpr (PART_F16) {
+#pragma unroll
+      for (int e = 0; e < E / 2; ++e) {
+        const halfx2 hh = __builtin_bit_cast(halfx2, w[e]);
+        o[2 * e] = fmaf(static_cast<float>(hh[0]), weight, o[2 * e]);
+        o[2 * e + 1] = fmaf(static_cast<float>(hh[1]), weight, o[2 * e + 1]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) o[e] = fmaf(__uint_as_float(w[e]), weight, o[e]);
+    }
+  };
+  auto load_ml = [&](int s) {
+    float2 ml = make_float2(-INFINITY, 0.f);
+    if (s < p.S) ml = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(s) * n_rows + row) * 2);
+    if (!(ml.y > 0.f)) ml = make_float2(-INFINITY, 0.f);     // an empty split contributes nothing
+    return ml;
+  };
+  float2 ml_pre[kPre / kRound];
+#pragma unroll
+  for (int r = 0; r < kPre / kRound; ++r) ml_pre[r] = load_ml(r * kRound + li);
+  uint32_t pre[kPre][PW];
+  {
+    const uint32_t* src = po_words;
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) {
+      if (u < p.S) fetch_from(src, pre[u]);
+      src += split_words;
+    }
+  }
+
+  {
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < kParPerThread; ++i) {
+      const int idx = threadIdx.x + i * kThreads;
+      if (idx < p.T) {
+        parent_lds[idx] = par_reg[i];
+        bad |= (par_reg[i] >= idx) || (par_reg[i] < -1);
+      }
+    }
+    if (blockIdx.x == 0) {
+      // single writer of the status word: 1 if any parent index is not a topological one
+      __shared__ int any_bad;
+      if (threadIdx.x == 0) any_bad = 0;
+      __syncthreads();
+      if (bad) any_bad = 1;
+      __syncthreads();
+      if (threadIdx.x == 0) *p.status = any_bad;
+    } else {
+      __syncthreads();
+    }
+  }
+
+  // ancestor chain of the row's node, eight per batch; the first batch's K/V rows are
+  // requested here.  A malformed parent entry ends the walk (the node is then treated as
+  // a root).  A group that has run out of ancestors keeps going with weight zero.
+  int a = t;
+  int anc[8];
+  uint32_t kraw[8][IN_BF16 ? E / 2 : E], vraw[8][IN_BF16 ? E / 2 : E];
+  constexpr int RW = IN_BF16 ? E / 2 : E;        // 32-bit words a lane holds per K or V row
+  auto request_batch = [&]() {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      anc[u] = a;
+      if (a >= 0) {
+        const int par = parent_lds[a];
+        a = (par >= a || par < -1) ? -1 : par;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (__any(anc[u] >= 0)) {
+        const int64_t off = g * p.kt_sh + max(anc[u], 0) * p.kt_st + li * E;
+        const uint32_t* ksrc = IN_BF16 ? reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(p.kt) + off)
+                                       : reinterpret_cast<const uint32_t*>(static_cast<const float*>(p.kt) + off);
+        const uint32_t* vsrc = IN_BF16 ? reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(p.vt) + off)
+                                       : reinterpret_cast<const uint32_t*>(static_cast<const float*>(p.vt) + off);
+#pragma unroll
+        for (int e = 0; e < RW; e += 2) {
+          const uint2 kx = *reinterpret_cast<const uint2*>(ksrc + e), vx = *reinterpret_cast<const uint2*>(vsrc + e);
+          kraw[u][e] = kx.x; kraw[u][e + 1] = kx.y;
+          vraw[u][e] = vx.x; vraw[u][e + 1] = vx.y;
+        }
+      }
+    }
+  };
+  auto unpack_row = [&](const uint32_t (&w)[RW], float (&v)[E]) {
+    if constexpr (IN_BF16) {
+#pragma unroll
+      for (int e = 0; e < E / 2; ++e) {
+        v[2 * e] = __uint_as_float(w[e] << 16);
+        v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+      }
     } else {
 #pragma unroll
       for (int e = 0; e < E; ++e) v[e] = __uint_as_float(w[e]);
     }
   };
-  float2 ml_first = make_float2(-INFINITY, 0.f);
-  if (lane < p.S) ml_first = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(lane) * n_rows + row) * 2);
-  uint32_t pre[kPre][PE];
-#pragma unroll
-  for (int u = 0; u < kPre; ++u) {
-    if (u < p.S) fetch(u, pre[u]);
-  }
+  request_batch();
 
-  float q[E], o[E];
-  load_vec<D, IN_BF16>(p.q, t * p.q_st + h * p.q_sh, lane, q);
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     q[e] *= p.scale_log2;
@@ -99,132 +220,112 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
   }
   float run_max = -INFINITY, run_sum = 0.f;
 
-  // tree part: node t and its ancestors.  The parent array (at most 128 entries) is
-  // held two per lane and the chain is walked with cross-lane reads, without touching
-  // memory; the ancestors' K/V rows are then fetched eight at a time so that their
-  // load latencies overlap.  A malformed entry ends the walk (the node is then
-  // treated as a root).
-  const int par_lo = lane < p.T ? p.parent[lane] : -1;
-  const int par_hi = lane + 64 < p.T ? p.parent[lane + 64] : -1;
-  int a = t;
-  while (a >= 0) {
-    int anc[8];
-    int n_anc = 0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      anc[u] = a;
-      if (a >= 0) {
-        ++n_anc;
-        const int par = a < 64 ? __builtin_amdgcn_readlane(par_lo, a) : __builtin_amdgcn_readlane(par_hi, a - 64);
-        a = (par >= a || par < -1) ? -1 : par;
-      }
-    }
-    float kk[8][E], vv[8][E];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (u < n_anc) {
-        load_vec<D, IN_BF16>(p.kt, g * p.kt_sh + anc[u] * p.kt_st, lane, kk[u]);
-        load_vec<D, IN_BF16>(p.vt, g * p.kt_sh + anc[u] * p.kt_st, lane, vv[u]);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (u < n_anc) {
-        float dot = 0.f;
-#pragma unroll
-        for (int e = 0; e < E; ++e) dot = fmaf(q[e], kk[u][e], dot);
-        const float s = wave_sum(dot);
-        const float new_max = fmaxf(run_max, s);
-        const float alpha = exp2f(run_max - new_max);
-        const float pr = exp2f(s - new_max);
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[e] = fmaf(pr, vv[u][e], o[e] * alpha);
-        run_sum = fmaf(run_sum, alpha, pr);
-        run_max = new_max;
-      }
-    }
-  }
-
-  // prefix splits.  Lane s first takes (max, sum) of split s (64 splits per round), the
-  // wave agrees on the common maximum, and lane s keeps the weight exp2(max_s - max_total)
-  // of its split.  The partial outputs are then added in split order with the weights
-  // broadcast from their lanes; the loads do not depend on one another, so several
-  // are in flight at once.  Fixed order, no atomics: bit-reproducible.
-  for (int s0 = 0; s0 < p.S; s0 += 64) {
-    const int s_mine = s0 + lane;
-    float ms = -INFINITY, ls = 0.f;
-    if (s_mine < p.S) {
-      const float2 ml = s0 == 0 ? ml_first
-                                : *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(s_mine) * n_rows + row) * 2);
-      if (ml.y > 0.f) {              // an empty split contributes nothing
-        ms = ml.x;
-        ls = ml.y;
-      }
-    }
-    const float new_max = fmaxf(run_max, wave_max(ms));
-    if (new_max == -INFINITY) continue;          // nothing so far and nothing in this round (wave-uniform)
-    const float alpha = exp2f(run_max - new_max);
-    const float w = ls > 0.f ? exp2f(ms - new_max) : 0.f;
+  // prefix splits, 16 per round.  Lane i of a group holds (max, sum) of split s0 + i, the
+  // group agrees on the common maximum, and lane i keeps the weight of its split.  The
+  // partial outputs are then added in split order with the weights fetched from their
+  // lanes.  Fixed order, no atomics: bit-reproducible.
+  auto merge_round = [&](float2 ml, int s0, auto&& partial_of) {
+    const float ms = ml.x, ls = ml.y;
+    const float new_max = fmaxf(run_max, row16_max(ms));
+    const bool any = new_max > -INFINITY;          // false only while nothing has been seen at all
+    const float alpha = any ? fast_exp2(run_max - new_max) : 1.f;
+    const float wsum = ls > 0.f ? ls * fast_exp2(ms - new_max) : 0.f;      // the split's share of the row sum
+    const float w = PART_F16 ? wsum : (ls > 0.f ? fast_exp2(ms - new_max) : 0.f);
     run_max = new_max;
-    run_sum = fmaf(run_sum, alpha, wave_sum(ls * w));
+    run_sum = fmaf(run_sum, alpha, row16_sum(wsum));
 #pragma unroll
     for (int e = 0; e < E; ++e) o[e] *= alpha;
-    const int s_end = min(64, p.S - s0);
-    int s = 0;
-    if (s0 == 0) {                   // the preloaded partials, in split order
+    partial_of(w, min(kRound, p.S - s0));
+  };
 #pragma unroll
-      for (int u = 0; u < kPre; ++u) {
-        if (u < s_end) {
-          const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
-          float v[E];
-          decode(pre[u], v);
+  for (int r = 0; r < kPre / kRound; ++r) {
+    if (r * kRound < p.S) {
+      merge_round(ml_pre[r], r * kRound, [&](float w, int s_end) {
 #pragma unroll
-          for (int e = 0; e < E; ++e) o[e] = fmaf(v[e], wu, o[e]);
+        for (int u = 0; u < kRound; ++u) {
+          if (u < s_end) accumulate(pre[r * kRound + u], lane_read(w, grp0 + u));
         }
+      });
+    }
+  }
+  for (int s0 = kPre; s0 < p.S; s0 += kRound) {
+    merge_round(load_ml(s0 + li), s0, [&](float w, int s_end) {
+      int s = 0;
+      for (; s + 8 <= s_end; s += 8) {
+        uint32_t raw[8][PW];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) fetch(s0 + s + u, raw[u]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) accumulate(raw[u], lane_read(w, grp0 + s + u));
       }
-      s = min(kPre, s_end);
-    }
-    for (; s + 8 <= s_end; s += 8) {
-      uint32_t raw[8][PE];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) fetch(s0 + s + u, raw[u]);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), s + u));
-        float v[E];
-        decode(raw[u], v);
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[e] = fmaf(v[e], wu, o[e]);
+      for (; s < s_end; ++s) {
+        uint32_t raw[PW];
+        fetch(s0 + s, raw);
+        accumulate(raw, lane_read(w, grp0 + s));
       }
-    }
-    for (; s < s_end; ++s) {
-      const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), s));
-      uint32_t raw[PE];
-      fetch(s0 + s, raw);
-      float v[E];
-      decode(raw, v);
-#pragma unroll
-      for (int e = 0; e < E; ++e) o[e] = fmaf(v[e], wu, o[e]);
-    }
+    });
   }
 
+  // tree part: the batch's eight logits first (independent of one another), then one
+  // online-softmax step for the whole batch
+  while (true) {
+    float sc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      sc[u] = -INFINITY;
+      if (__any(anc[u] >= 0)) {
+        float kk[E];
+        unpack_row(kraw[u], kk);
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) dot = fmaf(q[e], kk[e], dot);
+        dot = row16_sum(dot);
+        if (anc[u] >= 0) sc[u] = dot;
+      }
+    }
+    float bm = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+    const float new_max = fmaxf(run_max, bm);      // finite: the first batch holds the node itself
+    const float alpha = fast_exp2(run_max - new_max);
+    run_max = new_max;
+    run_sum *= alpha;
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] *= alpha;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (__any(anc[u] >= 0)) {
+        const float pr = fast_exp2(sc[u] - new_max);
+        float vv[E];
+        unpack_row(vraw[u], vv);
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] = fmaf(pr, vv[e], o[e]);
+        run_sum += pr;
+      }
+    }
+    if (!__any(a >= 0)) break;
+    request_batch();
+  }
+
+  if (!live) return;
   const float inv = 1.f / run_sum;
-  const int64_t ooff = t * p.o_st + h * p.o_sh + lane * E;
+  const int64_t ooff = t * p.o_st + h * p.o_sh + li * E;
   if (p.out_dtype == SPECEXT_BF16) {
-    uint16_t* ob = static_cast<uint16_t*>(p.out) + ooff;
-    if (E == 2) {
-      const uint32_t w = static_cast<uint32_t>(float_to_bf16_bits(o[0] * inv)) |
-                         (static_cast<uint32_t>(float_to_bf16_bits(o[E - 1] * inv)) << 16);
-      *reinterpret_cast<uint32_t*>(ob) = w;
+    uint32_t w[E / 2];
+#pragma unroll
+    for (int e = 0; e < E / 2; ++e)
+      w[e] = static_cast<uint32_t>(float_to_bf16_bits(o[2 * e] * inv)) |
+             (static_cast<uint32_t>(float_to_bf16_bits(o[2 * e + 1] * inv)) << 16);
+    uint32_t* ob = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(p.out) + ooff);
+    if (E == 8) {
+      *reinterpret_cast<uint4*>(ob) = make_uint4(w[0], w[1], w[E / 2 - 2], w[E / 2 - 1]);
     } else {
-      ob[0] = float_to_bf16_bits(o[0] * inv);
+      *reinterpret_cast<uint2*>(ob) = make_uint2(w[0], w[1]);
     }
   } else {
-    float* of = static_cast<float*>(p.out) + ooff;
+    float4* of = reinterpret_cast<float4*>(static_cast<float*>(p.out) + ooff);
 #pragma unroll
-    for (int e = 0; e < E; ++e) of[e] = o[e] * inv;
+    for (int e = 0; e < E / 4; ++e) of[e] = make_float4(o[4 * e] * inv, o[4 * e + 1] * inv, o[4 * e + 2] * inv, o[4 * e + 3] * inv);
   }
-  if (lane == 0) {
+  if (li == 0) {
     const float l2 = run_max + log2f(run_sum);
     p.lse2[row] = l2;
     if (p.lse) p.lse[h * p.T + t] = l2 * kLn2;
@@ -235,12 +336,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
 
 hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream) {
   const int n_rows = p.Hq * p.T;
-  dim3 grid((n_rows + kWavesPerBlock - 1) / kWavesPerBlock);
+  dim3 grid((n_rows + kRowsPerBlock - 1) / kRowsPerBlock);
   dim3 block(kWavesPerBlock * 64);
   const bool bf16 = p.in_dtype == SPECEXT_BF16;
-  if (p.part_bf16 && !(p.d == 128 && bf16)) return hipErrorInvalidValue;
+  if (p.part_f16 && !(p.d == 128 && bf16)) return hipErrorInvalidValue;
   if (p.d == 128) {
-    if (p.part_bf16) tree_merge_kernel<128, true, true><<<grid, block, 0, stream>>>(p);
+    if (p.part_f16) tree_merge_kernel<128, true, true><<<grid, block, 0, stream>>>(p);
     else if (bf16) tree_merge_kernel<128, true, false><<<grid, block, 0, stream>>>(p);
     else tree_merge_kernel<128, false, false><<<grid, block, 0, stream>>>(p);
   } else {

@@ -225,10 +225,10 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     const int key0 = tile_key0(j);
     const int first_row = tile_first_row(j);
     if (first_row < key0) {          // rows of a shifted last tile that belong to the tile before
+      const int thr = key0 - first_row - 4 * hf;     // register r holds key first_row + 4*hf + 8*(r/4) + r%4
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int key = first_row + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (key < key0) s[r] = -INFINITY;
+        if (8 * (r >> 2) + (r & 3) < thr) s[r] = -INFINITY;
       }
     }
     float mx = fmaxf(s[0], s[1]);

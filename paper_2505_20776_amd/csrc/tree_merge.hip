@@ -2,11 +2,12 @@
 //
 // Sixteen lanes per query row (tree node t of query head h), four rows per
 // wavefront; a lane holds D/16 consecutive elements of the head dimension.  Each
-// group of 16 lanes first walks its node's ancestor chain through parent[] (the
-// tree mask lets a node see itself and its ancestors only) with an online
-// softmax, then folds in the prefix splits in split order, each weighted by
-// exp2(max_split - max_total).  The merge is a fixed-order fp32 reduction: no
-// atomics, bit-reproducible from run to run.
+// group of 16 lanes folds in the prefix splits in split order, each weighted by
+// exp2(max_split - max_total), and walks its node's ancestor chain through parent[]
+// (the tree mask lets a node see itself and its ancestors only) with an online
+// softmax over batches of eight ancestors.  The order of these steps is fixed
+// (first 16 splits, tree part, remaining splits) and every sum is an fp32
+// reduction in a fixed order: no atomics, bit-reproducible from run to run.
 //
 // The prefix kernels leave one partial per (split, row): (max, sum) in base-2 units
 // plus either the unnormalised output in fp32, or (row-split matrix-core kernel)
@@ -57,7 +58,11 @@ __device__ __forceinline__ float lane_read(float v, int src) {
   return __int_as_float(__builtin_amdgcn_ds_bpermute(src << 2, __float_as_int(v)));
 }
 
-template <int D, bool IN_BF16, bool PART_F16>
+// HAS_PREFIX: at least one prefix split exists (p.S > 0).  It is a template parameter so that the
+// up-front loads below are issued without branches around them: with branches the
+// compiler can no longer count which loads are still pending and waits for all of them
+// where only the first is needed.
+template <int D, bool IN_BF16, bool PART_F16, bool HAS_PREFIX>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnParams p) {
   constexpr int E = D / 16;                      // elements per lane: 8 or 4
   static_assert(!PART_F16 || D == 128, "fp16 partials are written for head_dim 128 only");
@@ -78,16 +83,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
   const int row_raw = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 4);
   const bool live = row_raw < n_rows;
   const int row = live ? row_raw : n_rows - 1;   // groups past the end repeat the last row and store nothing
-  const int g = row / p.M;
+  // row = g * M + t * G + (head within the group); the quotients through a float
+  // reciprocal, exact for rows below 2^20 (the ABI caps n_q_heads * n_tree there)
+  const int g = static_cast<int>((static_cast<float>(row) + 0.5f) * (1.0f / static_cast<float>(p.M)));
   const int m = row - g * p.M;
-  const int t = m / p.G;
-  const int h = g * p.G + m % p.G;
+  const int t = static_cast<int>((static_cast<float>(m) + 0.5f) * (1.0f / static_cast<float>(p.G)));
+  const int h = g * p.G + (m - t * p.G);
 
   // Everything below is ordered so that no wait is longer than it must be: loads return in
   // issue order, so the parent array (first, above) is followed by the query, the
-  // (max, sum) pairs and the first kPre split partials, which depend on nothing, and only
-  // then, once the ancestor chain is known, by the tree K/V rows.  The arithmetic takes
-  // the same order: prefix splits first (in split order), tree part last.
+  // (max, sum) pairs and the first 16 split partials, which depend on nothing; then, once
+  // the ancestor chain is known, come the tree K/V rows and behind them the next 16
+  // partials (a compute unit takes in only about 16 bytes per clock, so a longer burst
+  // would only block the wave at the load queue).  The arithmetic takes the same order.
   float q[E], o[E];
   load_row_part<E, IN_BF16>(p.q, t * p.q_st + h * p.q_sh + li * E, q);
   constexpr int kRound = 16;                     // splits whose (max, sum) one group holds, one per lane
@@ -124,24 +132,31 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
       for (int e = 0; e < E; ++e) o[e] = fmaf(__uint_as_float(w[e]), weight, o[e]);
     }
   };
+  // (max, sum) of split s; splits past the end read the last split and count as empty
   auto load_ml = [&](int s) {
-    float2 ml = make_float2(-INFINITY, 0.f);
-    if (s < p.S) ml = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(s) * n_rows + row) * 2);
-    if (!(ml.y > 0.f)) ml = make_float2(-INFINITY, 0.f);     // an empty split contributes nothing
+    const int sc = min(s, p.S - 1);
+    float2 ml = *reinterpret_cast<const float2*>(p.part_ml + (static_cast<int64_t>(sc) * n_rows + row) * 2);
+    if (s >= p.S || !(ml.y > 0.f)) ml = make_float2(-INFINITY, 0.f);     // an empty split contributes nothing
     return ml;
   };
   float2 ml_pre[kPre / kRound];
-#pragma unroll
-  for (int r = 0; r < kPre / kRound; ++r) ml_pre[r] = load_ml(r * kRound + li);
   uint32_t pre[kPre][PW];
-  {
-    const uint32_t* src = po_words;
+  if (HAS_PREFIX) {
 #pragma unroll
-    for (int u = 0; u < kPre; ++u) {
-      if (u < p.S) fetch_from(src, pre[u]);
-      src += split_words;
-    }
+    for (int r = 0; r < kPre / kRound; ++r) ml_pre[r] = load_ml(r * kRound + li);
   }
+  // splits past the end fetch the last split again (never used)
+  const uint32_t* pre_src = po_words;
+  const uint32_t* const pre_last = po_words + (p.S - 1) * split_words;
+  auto request_partials = [&](auto first_c) {      // kRound of them, starting at split FIRST
+    constexpr int first = decltype(first_c)::value;
+#pragma unroll
+    for (int u = first; u < first + kRound; ++u) {
+      fetch_from(pre_src, pre[u]);
+      if (pre_src != pre_last) pre_src += split_words;
+    }
+  };
+  if (HAS_PREFIX) request_partials(std::integral_constant<int, 0>{});
 
   {
     bool bad = false;
@@ -212,6 +227,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
     }
   };
   request_batch();
+  // the second half of the up-front partials goes behind the K/V rows: by now the
+  // first half has drained from the load queue, and it is not needed before the tree part
+  if (HAS_PREFIX && kPre > kRound) request_partials(std::integral_constant<int, kPre - kRound>{});
 
 #pragma unroll
   for (int e = 0; e < E; ++e) {
@@ -237,9 +255,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
     for (int e = 0; e < E; ++e) o[e] *= alpha;
     partial_of(w, min(kRound, p.S - s0));
   };
-#pragma unroll
-  for (int r = 0; r < kPre / kRound; ++r) {
-    if (r * kRound < p.S) {
+  auto merge_preloaded = [&](auto r_c) {
+    constexpr int r = decltype(r_c)::value;
+    if (HAS_PREFIX && r * kRound < p.S) {
       merge_round(ml_pre[r], r * kRound, [&](float w, int s_end) {
 #pragma unroll
         for (int u = 0; u < kRound; ++u) {
@@ -247,24 +265,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
         }
       });
     }
-  }
-  for (int s0 = kPre; s0 < p.S; s0 += kRound) {
-    merge_round(load_ml(s0 + li), s0, [&](float w, int s_end) {
-      int s = 0;
-      for (; s + 8 <= s_end; s += 8) {
-        uint32_t raw[8][PW];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) fetch(s0 + s + u, raw[u]);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) accumulate(raw[u], lane_read(w, grp0 + s + u));
-      }
-      for (; s < s_end; ++s) {
-        uint32_t raw[PW];
-        fetch(s0 + s, raw);
-        accumulate(raw, lane_read(w, grp0 + s));
-      }
-    });
-  }
+  };
+  merge_preloaded(std::integral_constant<int, 0>{});
 
   // tree part: the batch's eight logits first (independent of one another), then one
   // online-softmax step for the whole batch
@@ -305,6 +307,25 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
     request_batch();
   }
 
+  if (kPre > kRound) merge_preloaded(std::integral_constant<int, (kPre > kRound ? 1 : 0)>{});
+  for (int s0 = kPre; HAS_PREFIX && s0 < p.S; s0 += kRound) {
+    merge_round(load_ml(s0 + li), s0, [&](float w, int s_end) {
+      int s = 0;
+      for (; s + 8 <= s_end; s += 8) {
+        uint32_t raw[8][PW];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) fetch(s0 + s + u, raw[u]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) accumulate(raw[u], lane_read(w, grp0 + s + u));
+      }
+      for (; s < s_end; ++s) {
+        uint32_t raw[PW];
+        fetch(s0 + s, raw);
+        accumulate(raw, lane_read(w, grp0 + s));
+      }
+    });
+  }
+
   if (!live) return;
   const float inv = 1.f / run_sum;
   const int64_t ooff = t * p.o_st + h * p.o_sh + li * E;
@@ -340,14 +361,21 @@ hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream) {
   dim3 block(kWavesPerBlock * 64);
   const bool bf16 = p.in_dtype == SPECEXT_BF16;
   if (p.part_f16 && !(p.d == 128 && bf16)) return hipErrorInvalidValue;
+  const bool pre = p.S > 0;
+#define SPECEXT_LAUNCH(D_, BF_, F16_)                                                              \
+  do {                                                                                             \
+    if (pre) tree_merge_kernel<D_, BF_, F16_, true><<<grid, block, 0, stream>>>(p);                \
+    else tree_merge_kernel<D_, BF_, F16_, false><<<grid, block, 0, stream>>>(p);                   \
+  } while (0)
   if (p.d == 128) {
-    if (p.part_f16) tree_merge_kernel<128, true, true><<<grid, block, 0, stream>>>(p);
-    else if (bf16) tree_merge_kernel<128, true, false><<<grid, block, 0, stream>>>(p);
-    else tree_merge_kernel<128, false, false><<<grid, block, 0, stream>>>(p);
+    if (p.part_f16) SPECEXT_LAUNCH(128, true, true);
+    else if (bf16) SPECEXT_LAUNCH(128, true, false);
+    else SPECEXT_LAUNCH(128, false, false);
   } else {
-    if (bf16) tree_merge_kernel<64, true, false><<<grid, block, 0, stream>>>(p);
-    else tree_merge_kernel<64, false, false><<<grid, block, 0, stream>>>(p);
+    if (bf16) SPECEXT_LAUNCH(64, true, false);
+    else SPECEXT_LAUNCH(64, false, false);
   }
+#undef SPECEXT_LAUNCH
   return hipGetLastError();
 }
 

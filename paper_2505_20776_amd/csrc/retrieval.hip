@@ -1,7 +1,7 @@
 // Cross-model Retrieval kernels (SpecExtend Sec. 3.2.1 and Alg. 1):
 //   chunk_scores_kernel  - normalise the per-chunk exponential sums left by
 //                          the prefix pass, average over chunk tokens and heads
-//   select_kernel        - SelectChunks: top-k by radix select, ascending output
+//   select_*_kernel      - SelectChunks: top-k by ranking (short inputs) or radix select, ascending output
 //   gather_*_kernel      - UpdateDraftCache: copy the chosen chunks verbatim
 #include "common.h"
 
@@ -178,6 +178,60 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
   }
 }
 
+// Short inputs (n <= kRankMax, one key per thread): every thread ranks its own key
+// against all the others, which sit in LDS and are read four at a time by broadcast.
+// rank(i) = #{j : key_j > key_i} + #{j < i : key_j == key_i} (ties go to the lower
+// index); a key is kept when rank < k.  Two barriers in all, against the one per key
+// bit of the radix search above.  The output order comes from ballot prefix counts.
+constexpr int kRankMax = 1024;
+
+__global__ __launch_bounds__(kRankMax) void select_rank_kernel(const float* __restrict__ scores, int n, int k,
+                                                              int* __restrict__ idx_out, int* __restrict__ n_out) {
+  __shared__ __attribute__((aligned(16))) uint32_t keys[kRankMax];
+  __shared__ int wave_takes[kRankMax / 64];
+  const int i = threadIdx.x;
+  const int lane = i & 63;
+  const int wave = i >> 6;
+  const int k_eff = min(k, n);
+  if (i == 0) *n_out = k_eff;
+  for (int u = k_eff + i; u < k; u += blockDim.x) idx_out[u] = -1;
+  if (k_eff == 0) return;
+  // keys are kept >= 1 so that "key - 1" below cannot wrap; padding slots hold 0, below every key
+  const uint32_t mine = i < n ? max(orderable(scores[i]), 1u) : 0u;
+  keys[i] = mine;
+  __syncthreads();
+  const int n4 = (n + 3) & ~3;                   // blockDim.x is a multiple of 64, so the padding exists
+  // key_j counts against thread i when key_j > key_i, or key_j == key_i and j < i: that is
+  // key_j > key_i - 1 for j < i and key_j > key_i for j > i.  For the j of earlier waves the
+  // first form holds for the whole wave, for those of later waves the second; only inside
+  // the thread's own wave does it depend on the lane.
+  const uint32_t below = mine - 1u;
+  int rank = 0;
+  const int own_lo = wave * 64, own_hi = own_lo + 64;
+  for (int j = 0; j < min(own_lo, n4); j += 4) {
+    const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+    rank += (kj.x > below) + (kj.y > below) + (kj.z > below) + (kj.w > below);
+  }
+  for (int j = own_lo; j < min(own_hi, n4); j += 4) {
+    const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+    rank += (kj.x > (j < i ? below : mine)) + (kj.y > (j + 1 < i ? below : mine)) + (kj.z > (j + 2 < i ? below : mine)) +
+            (kj.w > (j + 3 < i ? below : mine));
+  }
+  for (int j = own_hi; j < n4; j += 4) {
+    const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+    rank += (kj.x > mine) + (kj.y > mine) + (kj.z > mine) + (kj.w > mine);
+  }
+  const bool take = i < n && rank < k_eff;
+  const uint64_t bal = __ballot(take);
+  if (lane == 0) wave_takes[wave] = __popcll(bal);
+  __syncthreads();
+  if (take) {
+    int pos = __popcll(bal & ((uint64_t{1} << lane) - 1));
+    for (int w = 0; w < wave; ++w) pos += wave_takes[w];
+    idx_out[pos] = i;
+  }
+}
+
 // --------------------------------------------------------------------------
 // draft-KV gather
 // --------------------------------------------------------------------------
@@ -259,7 +313,11 @@ hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k
                                 int32_t* n_out, hipStream_t stream) {
   // a small input needs only as many waves as it has scores (fewer waves, cheaper barriers)
   const int threads = n_chunks >= kSelThreads ? kSelThreads : ((n_chunks + 63) / 64) * 64;
-  select_kernel<<<dim3(1), dim3(threads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
+  if (n_chunks <= kRankMax) {
+    select_rank_kernel<<<dim3(1), dim3(threads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
+  } else {
+    select_kernel<<<dim3(1), dim3(threads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
+  }
   return hipGetLastError();
 }
 

@@ -230,7 +230,7 @@ def test_run_to_run_bit_identical(hx):
 # --------------------------------------------------------------------------
 
 @pytest.mark.parametrize("n,k", [(1, 1), (16, 4), (64, 32), (512, 32), (512, 512), (512, 600), (1000, 0),
-                                 (4097, 100), (65536, 2048)])
+                                 (1024, 77), (1025, 77), (4097, 100), (65536, 2048)])
 def test_select_exact(hx, n, k):
     rng = np.random.default_rng(n + k)
     s = rng.random(n).astype(np.float32)

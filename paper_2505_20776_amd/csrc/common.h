@@ -39,7 +39,7 @@ struct AttnParams {
   int32_t score_gran, n_sub;      // keys per score block (32 on the MFMA path, else B) and their count
   int32_t use_mfma;               // 0 vector-ALU kernel, 1 matrix-core key-split kernel, 2 matrix-core row-split kernel
   int32_t rows_per_group;         // query rows of one KV head that one workgroup covers
-  int32_t part_f16;               // 1: part_o holds O/l as fp16 [S][rows][d] (row-split kernel), 0: unnormalised O as fp32
+  int32_t part_f16;               // part_o [S][rows][d] holds the unnormalised O as fp16 (1: row-split kernel) or fp32 (0)
   int32_t in_dtype, out_dtype;
   float scale_log2;
   int64_t q_st, q_sh, kp_sh, kp_sl, kt_sh, kt_st, o_st, o_sh;

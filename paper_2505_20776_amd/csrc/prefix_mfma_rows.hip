@@ -300,15 +300,23 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     });
   }
 
-  // ---- partial results of this split: O divided by its row sum, as fp16 (clamped to the
-  // fp16 range: a convex combination of V rows, so only |V| beyond 65504 would clip),
-  // with the reference (base-2 units) and the row sum in fp32.  O^T sits in registers
-  // with a lane owning one row; it goes through the wave's private LDS area so that the
-  // global stores are whole 256-byte rows.
+  // ---- partial results of this split: the triple (reference, row sum, unnormalised O)
+  // is rescaled by the power of two that brings the row's largest |O| just below 1
+  // (O * 2^-e, sum * 2^-e, reference + e describe the same partial), and O goes out as
+  // fp16: every row keeps 11 bits against its own largest element whatever the scale of
+  // V.  O^T sits in registers with a lane owning one row; it goes through the wave's
+  // private LDS area so that the global stores are whole 256-byte rows.
   const float l_tot = halves_sum(run_sum);
-  const float inv_l = 1.0f / l_tot;
+  float row_max = 0.f;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) row_max = fmaxf(row_max, fmaxf(fabsf(acc_o[db][r]), fabsf(acc_o[db][r + 1])));
+  row_max = halves_max(row_max);
+  const int row_exp = (row_max > 0.f && row_max < INFINITY) ? __builtin_amdgcn_frexp_expf(row_max) : 0;
+  const float row_scale = __builtin_amdgcn_ldexpf(1.0f, -row_exp);
   auto to_half2 = [&](float x, float y) {
-    const floatx2 f = {__builtin_amdgcn_fmed3f(x * inv_l, -65504.f, 65504.f), __builtin_amdgcn_fmed3f(y * inv_l, -65504.f, 65504.f)};
+    const floatx2 f = {x * row_scale, y * row_scale};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, halfx2));
   };
   const int64_t slot0 = static_cast<int64_t>(split) * p.Hq * p.T + g * p.M + row0;     // slot of the wave's first row
@@ -335,8 +343,8 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       *reinterpret_cast<uintx4*>(part_h + (slot0 + row) * kD + 8 * (lane & 15)) = uintx4{a[0], a[1], b[0], b[1]};
   }
   if (hf == 0 && m < p.M) {
-    p.part_ml[(slot0 + c32) * 2] = ref * c;
-    p.part_ml[(slot0 + c32) * 2 + 1] = l_tot;
+    p.part_ml[(slot0 + c32) * 2] = ref * c + static_cast<float>(row_exp);
+    p.part_ml[(slot0 + c32) * 2 + 1] = l_tot * row_scale;
   }
 }
 

@@ -10,8 +10,8 @@
 // reduction in a fixed order: no atomics, bit-reproducible from run to run.
 //
 // The prefix kernels leave one partial per (split, row): (max, sum) in base-2 units
-// plus either the unnormalised output in fp32, or (row-split matrix-core kernel)
-// the output already divided by its sum, in fp16.
+// plus the unnormalised output, in fp32 or (row-split matrix-core kernel, which first
+// rescales the triple by a power of two per row) in fp16.
 #include "common.h"
 
 namespace specext {
@@ -247,8 +247,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
     const float new_max = fmaxf(run_max, row16_max(ms));
     const bool any = new_max > -INFINITY;          // false only while nothing has been seen at all
     const float alpha = any ? fast_exp2(run_max - new_max) : 1.f;
-    const float wsum = ls > 0.f ? ls * fast_exp2(ms - new_max) : 0.f;      // the split's share of the row sum
-    const float w = PART_F16 ? wsum : (ls > 0.f ? fast_exp2(ms - new_max) : 0.f);
+    const float w = ls > 0.f ? fast_exp2(ms - new_max) : 0.f;             // weight of the split's unnormalised output
+    const float wsum = ls * w;                                             // the split's share of the row sum
     run_max = new_max;
     run_sum = fmaf(run_sum, alpha, row16_sum(wsum));
 #pragma unroll

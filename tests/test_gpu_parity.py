@@ -226,6 +226,25 @@ def test_run_to_run_bit_identical(hx):
 
 
 # --------------------------------------------------------------------------
+# scale of V: the split partials cross HBM as fp16 after a per-row power-of-two
+# rescale, so the output must follow V through any power of two (exactly representable
+# in bf16) with the same relative accuracy
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("log2_scale", [-40, 24, 100])
+def test_value_scale(hx, log2_scale):
+    import dataclasses
+    wl = config_workload(2, sharp=True)
+    ref_out, ref_lse, _ = oracle_all(wl)
+    f = np.float32(2.0) ** log2_scale
+    big = dataclasses.replace(wl, v_prefix=wl.v_prefix * f, v_tree=wl.v_tree * f)
+    res = hx.run_verify(big, want_scores=False)
+    assert res["status"] == 0
+    res["out"] = (res["out"].astype(np.float64) / float(f)).astype(np.float32)
+    check_attention(wl, res, ref_out, ref_lse, f"V x 2^{log2_scale}")
+
+
+# --------------------------------------------------------------------------
 # SelectChunks on its own: bit-exact against the oracle on the same fp32 values
 # --------------------------------------------------------------------------
 

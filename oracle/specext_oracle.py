@@ -33,6 +33,19 @@ chunk / tree permutation laws; GQA duplication; top-k versus brute-force
 subset search; gather round trips; literal-loop brute force on tiny inputs.
 The paper prints no worked numeric example for any of these quantities, so
 beyond those pins the numeric values are "parity unpinned by the paper".
+
+Closing the step (what follows the attention in Alg. 1): `accept_greedy` is the
+Verify / Correct loop of Alg. 1 at temperature 0 - a drafted token is accepted
+exactly when it equals the target model's arg-max token for its position, the
+first mismatch is replaced by that arg-max token, and when every drafted token
+on the path is accepted the target's next arg-max token is appended - walked
+down the draft tree (tree attention, Sec. 2: the children of a node are
+alternative drafts for the position after it).  Readings: among several children
+with the accepted token the lowest node index wins; roots (parent -1) are the
+drafts for the first new position.  `commit_tree_kv` appends the accepted
+nodes' K/V rows to the target cache behind the prefix, byte for byte.  Pins:
+the chain tree against the literal sequential loop of Alg. 1, a recursive
+reformulation on random trees, maximality and chain invariants.
 """
 from __future__ import annotations
 
@@ -40,7 +53,7 @@ import numpy as np
 
 __all__ = [
     "ancestor_mask", "verify_attention", "chunk_scores", "hybrid_attention",
-    "select_chunks", "gather_draft_kv", "causal_attention_tail",
+    "select_chunks", "gather_draft_kv", "causal_attention_tail", "accept_greedy", "commit_tree_kv",
 ]
 
 
@@ -237,3 +250,41 @@ def gather_draft_kv(k_src, v_src, idx, chunk_size):
     k_dst = np.ascontiguousarray(k_src[:, :, pos, :])
     v_dst = np.ascontiguousarray(v_src[:, :, pos, :])
     return k_dst, v_dst, pos.astype(np.int32)
+
+
+def accept_greedy(parent, draft_token, target_token, first_target):
+    """Alg. 1 Verify / Correct at temperature 0 along the draft tree.
+
+    parent[i] < i (-1 = root): tree shape.  draft_token[i]: the token drafted at
+    node i.  target_token[i]: the target model's arg-max token for the position
+    after node i.  first_target: its arg-max token for the first new position.
+    Returns (path, next_token): the accepted nodes from the top down, and the
+    token that follows them (the correction of the first mismatch, or the bonus
+    token when a leaf was reached).
+    """
+    parent = np.asarray(parent)
+    draft_token = np.asarray(draft_token)
+    target_token = np.asarray(target_token)
+    path = []
+    cur, want = -1, int(first_target)
+    while True:
+        matches = [i for i in range(len(parent)) if parent[i] == cur and draft_token[i] == want]
+        if not matches:
+            return path, want
+        cur = min(matches)
+        path.append(cur)
+        want = int(target_token[cur])
+
+
+def commit_tree_kv(k_cache, v_cache, k_tree, v_tree, path, prefix_len):
+    """Accepted tree tokens enter the target cache: cache[:, prefix_len + i, :] = tree[:, path[i], :].
+
+    k_cache / v_cache [Hkv, capacity, d], k_tree / v_tree [Hkv, T, d]; returns the
+    updated copies and the new prefix length.  Verbatim copies (any dtype).
+    """
+    k_new = np.array(k_cache, copy=True)
+    v_new = np.array(v_cache, copy=True)
+    for i, node in enumerate(path):
+        k_new[:, prefix_len + i, :] = k_tree[:, node, :]
+        v_new[:, prefix_len + i, :] = v_tree[:, node, :]
+    return k_new, v_new, prefix_len + len(path)

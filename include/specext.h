@@ -11,6 +11,8 @@
  *     scores of one query token, top-k chunk selection (SelectChunks) and the
  *     compaction of the draft model's KV cache to the chosen chunks
  *     (UpdateDraftCache).
+ *   - The rest of the step in Alg. 1: greedy acceptance along the draft tree and
+ *     the commit of the accepted tokens' K/V rows into the target cache.
  *
  * Conventions common to every entry point
  *   - Every tensor argument is a DEVICE pointer owned by the caller.  The
@@ -180,6 +182,69 @@ int specext_gather_draft_kv(const void* k_src, const void* v_src, void* k_dst, v
                             int32_t n_layers, int32_t n_kv_heads, int32_t src_len, int32_t dst_cap,
                             int32_t head_dim, int32_t chunk_size, int32_t elem_bytes,
                             int32_t* pos_out, int32_t* len_out, void* stream);
+
+/*
+ * Verify / Correct of Alg. 1 at temperature 0, walked down the draft tree (the
+ * children of a node are the alternative drafts for the position after it, as in
+ * the tree attention of Sec. 2): starting above the roots with the token the
+ * target model wants first, the child that carries the wanted token is accepted
+ * (the lowest node index if several do) and the token the target wants after
+ * that child is wanted next; the walk ends at the first position where no child
+ * matches.
+ *
+ *   parent         int32 [n_tree], parent[i] < i, -1 = root; n_tree in [1, 128]
+ *   draft_token    int32 [n_tree]: the token drafted at each node
+ *   target_token   int32 [n_tree]: the target model's arg-max token for the
+ *                  position after each node
+ *   first_target   device int32 [1]: its arg-max token for the first new position
+ *   path_out       int32 [n_tree]: accepted nodes from the top down, then -1
+ *   n_accept_out   device int32 [1]: how many nodes were accepted (0 .. n_tree)
+ *   next_token_out device int32 [1]: the token that follows the accepted ones (the
+ *                  correction of the first mismatch, or the bonus token after a
+ *                  fully accepted path)
+ */
+int specext_accept_greedy(const int32_t* parent, const int32_t* draft_token, const int32_t* target_token,
+                          const int32_t* first_target, int32_t n_tree, int32_t* path_out,
+                          int32_t* n_accept_out, int32_t* next_token_out, void* stream);
+
+/*
+ * The accepted tree tokens enter the target model's KV cache (the step after
+ * verification in Alg. 1: x_{n+1} <- accepted token, n <- n + 1):
+ * cache[y, g, prefix_len + i, :] = tree[y, g, path[i], :] for i < n_accept, bytes
+ * verbatim, for K and for V, for every layer y in one launch.
+ *
+ *   k_tree, v_tree    [n_layers, n_kv_heads, n_tree, head_dim] elements of elem_bytes
+ *                     (the tree K/V that the layers' specext_verify_attn calls were given)
+ *   k_cache, v_cache  [n_layers, n_kv_heads, cache_capacity, head_dim]
+ *   path, n_accept    as written by specext_accept_greedy (device); entries outside
+ *                     [0, n_tree) are skipped, n_accept is clamped to max_accept
+ *   max_accept        launch bound on the accepted length (<= 128);
+ *                     prefix_len + max_accept must not exceed cache_capacity
+ *   *_stride_*        in elements; 0 = contiguous in the shapes above (separate
+ *                     per-layer allocations: one call per layer with n_layers = 1)
+ *
+ * head_dim * elem_bytes and every stride in bytes must be multiples of 16 and the
+ * four tensor pointers 16-byte aligned.
+ */
+int specext_commit_tree_kv(const void* k_tree, const void* v_tree, void* k_cache, void* v_cache,
+                           const int32_t* path, const int32_t* n_accept, int32_t max_accept, int32_t n_tree,
+                           int32_t n_layers, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes,
+                           int32_t prefix_len, int32_t cache_capacity, int64_t tree_stride_layer,
+                           int64_t tree_stride_h, int64_t tree_stride_t, int64_t cache_stride_layer,
+                           int64_t cache_stride_h, int64_t cache_stride_l, void* stream);
+
+/*
+ * specext_chunk_scores for the row of the last accepted token (Sec. 3.2.1: the
+ * query of the ranking is the last accepted token), read on the device so that no
+ * host round trip sits between acceptance and retrieval: scores the tree row
+ * path[*n_accept - 1], or row 0 when nothing was accepted.
+ *
+ *   desc, workspace   as for specext_chunk_scores
+ *   path, n_accept    as written by specext_accept_greedy (device)
+ *   scores            fp32 [C]
+ */
+int specext_chunk_scores_accepted(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                                  const int32_t* path, const int32_t* n_accept, float* scores, void* stream);
 
 /*
  * Number of prefix splits specext_verify_attn uses for this descriptor when

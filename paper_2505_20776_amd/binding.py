@@ -27,7 +27,8 @@ STATUS_NAMES = {0: "SPECEXT_OK", -1: "SPECEXT_ERR_INVALID_ARG", -2: "SPECEXT_ERR
                 -3: "SPECEXT_ERR_WORKSPACE_TOO_SMALL", -4: "SPECEXT_ERR_LAUNCH_FAILED"}
 
 EXPORTED = ("specext_strerror", "specext_workspace_bytes", "specext_num_splits", "specext_verify_attn",
-            "specext_chunk_scores", "specext_select_chunks", "specext_gather_draft_kv")
+            "specext_chunk_scores", "specext_select_chunks", "specext_gather_draft_kv", "specext_accept_greedy",
+            "specext_commit_tree_kv", "specext_chunk_scores_accepted")
 
 
 class SpecextError(RuntimeError):
@@ -78,6 +79,14 @@ def load_library() -> ctypes.CDLL:
     lib.specext_select_chunks.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.specext_gather_draft_kv.restype = ctypes.c_int
     lib.specext_gather_draft_kv.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    i64 = ctypes.c_int64
+    lib.specext_accept_greedy.restype = ctypes.c_int
+    lib.specext_accept_greedy.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.specext_commit_tree_kv.restype = ctypes.c_int
+    lib.specext_commit_tree_kv.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32,
+                                           i64, i64, i64, i64, i64, i64, vp]
+    lib.specext_chunk_scores_accepted.restype = ctypes.c_int
+    lib.specext_chunk_scores_accepted.argtypes = [dp, vp, sz, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -175,4 +184,41 @@ def gather_draft_kv(k_src, v_src, k_dst, v_dst, idx, n_idx, max_idx: int, n_laye
                                                 int(elem_bytes), _ptr(pos_out), _ptr(len_out), _stream(stream))
     if check:
         _check(rc, "specext_gather_draft_kv")
+    return rc
+
+
+def accept_greedy(parent, draft_token, target_token, first_target, n_tree: int, path_out, n_accept_out,
+                  next_token_out, stream=None, check: bool = True) -> int:
+    rc = load_library().specext_accept_greedy(_ptr(parent), _ptr(draft_token), _ptr(target_token), _ptr(first_target),
+                                              int(n_tree), _ptr(path_out), _ptr(n_accept_out), _ptr(next_token_out),
+                                              _stream(stream))
+    if check:
+        _check(rc, "specext_accept_greedy")
+    return rc
+
+
+def commit_tree_kv(k_tree, v_tree, k_cache, v_cache, path, n_accept, max_accept: int, n_tree: int, n_layers: int,
+                   n_kv_heads: int, head_dim: int, elem_bytes: int, prefix_len: int, cache_capacity: int,
+                   tree_stride_layer: int = 0, tree_stride_h: int = 0, tree_stride_t: int = 0,
+                   cache_stride_layer: int = 0, cache_stride_h: int = 0, cache_stride_l: int = 0, stream=None,
+                   check: bool = True) -> int:
+    rc = load_library().specext_commit_tree_kv(_ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache), _ptr(path),
+                                               _ptr(n_accept), int(max_accept), int(n_tree), int(n_layers),
+                                               int(n_kv_heads), int(head_dim), int(elem_bytes), int(prefix_len),
+                                               int(cache_capacity), int(tree_stride_layer), int(tree_stride_h),
+                                               int(tree_stride_t), int(cache_stride_layer), int(cache_stride_h),
+                                               int(cache_stride_l), _stream(stream))
+    if check:
+        _check(rc, "specext_commit_tree_kv")
+    return rc
+
+
+def chunk_scores_accepted(desc, workspace, path, n_accept, scores, workspace_nbytes: Optional[int] = None,
+                          stream=None, check: bool = True) -> int:
+    if workspace_nbytes is None:
+        workspace_nbytes = workspace.numel() * workspace.element_size()
+    rc = load_library().specext_chunk_scores_accepted(ctypes.byref(desc), _ptr(workspace), workspace_nbytes,
+                                                      _ptr(path), _ptr(n_accept), _ptr(scores), _stream(stream))
+    if check:
+        _check(rc, "specext_chunk_scores_accepted")
     return rc

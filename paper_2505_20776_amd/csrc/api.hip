@@ -241,7 +241,75 @@ int specext_chunk_scores(const specext_desc* desc, const void* workspace, size_t
   const WorkspaceLayout w = layout_of(p);
   if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
   bind_workspace(&p, w, const_cast<void*>(workspace));
-  if (launch_chunk_scores(p, score_row, scores, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch_chunk_scores(p, score_row, nullptr, nullptr, scores, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_chunk_scores_accepted(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                                  const int32_t* path, const int32_t* n_accept, float* scores, void* stream) {
+  AttnParams p;
+  const int rc = resolve(desc, &p);
+  if (rc != SPECEXT_OK) return rc;
+  if (!workspace || !scores || !path || !n_accept || !p.want_scores || p.C <= 0) return SPECEXT_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || (reinterpret_cast<uintptr_t>(scores) & 3u) ||
+      (reinterpret_cast<uintptr_t>(path) & 3u) || (reinterpret_cast<uintptr_t>(n_accept) & 3u))
+    return SPECEXT_ERR_UNSUPPORTED;
+  const WorkspaceLayout w = layout_of(p);
+  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  bind_workspace(&p, w, const_cast<void*>(workspace));
+  if (launch_chunk_scores(p, 0, path, n_accept, scores, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_accept_greedy(const int32_t* parent, const int32_t* draft_token, const int32_t* target_token,
+                          const int32_t* first_target, int32_t n_tree, int32_t* path_out, int32_t* n_accept_out,
+                          int32_t* next_token_out, void* stream) {
+  if (!parent || !draft_token || !target_token || !first_target || !path_out || !n_accept_out || !next_token_out ||
+      n_tree <= 0)
+    return SPECEXT_ERR_INVALID_ARG;
+  if (n_tree > SPECEXT_MAX_TREE) return SPECEXT_ERR_UNSUPPORTED;
+  const void* ptrs[] = {parent, draft_token, target_token, first_target, path_out, n_accept_out, next_token_out};
+  for (const void* q : ptrs)
+    if (reinterpret_cast<uintptr_t>(q) & 3u) return SPECEXT_ERR_UNSUPPORTED;
+  if (launch_accept_greedy(parent, draft_token, target_token, first_target, n_tree, path_out, n_accept_out,
+                           next_token_out, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_commit_tree_kv(const void* k_tree, const void* v_tree, void* k_cache, void* v_cache,
+                           const int32_t* path, const int32_t* n_accept, int32_t max_accept, int32_t n_tree,
+                           int32_t n_layers, int32_t n_kv_heads, int32_t head_dim, int32_t elem_bytes,
+                           int32_t prefix_len, int32_t cache_capacity, int64_t tree_stride_layer,
+                           int64_t tree_stride_h, int64_t tree_stride_t, int64_t cache_stride_layer,
+                           int64_t cache_stride_h, int64_t cache_stride_l, void* stream) {
+  if (!k_tree || !v_tree || !k_cache || !v_cache || !path || !n_accept) return SPECEXT_ERR_INVALID_ARG;
+  if (max_accept < 0 || n_tree <= 0 || n_layers <= 0 || n_kv_heads <= 0 || head_dim <= 0 || elem_bytes <= 0 ||
+      prefix_len < 0 || tree_stride_layer < 0 || tree_stride_h < 0 || tree_stride_t < 0 || cache_stride_layer < 0 ||
+      cache_stride_h < 0 || cache_stride_l < 0)
+    return SPECEXT_ERR_INVALID_ARG;
+  if (static_cast<int64_t>(prefix_len) + max_accept > cache_capacity) return SPECEXT_ERR_INVALID_ARG;
+  if (n_tree > SPECEXT_MAX_TREE || max_accept > SPECEXT_MAX_TREE ||
+      static_cast<int64_t>(n_layers) * n_kv_heads > 65535)
+    return SPECEXT_ERR_UNSUPPORTED;
+  const int64_t row_bytes = static_cast<int64_t>(head_dim) * elem_bytes;
+  const int64_t tst = (tree_stride_t ? tree_stride_t : head_dim) * elem_bytes;
+  const int64_t tsh = tree_stride_h ? tree_stride_h * elem_bytes : n_tree * tst;
+  const int64_t tsl = tree_stride_layer ? tree_stride_layer * elem_bytes : n_kv_heads * tsh;
+  const int64_t csl = (cache_stride_l ? cache_stride_l : head_dim) * elem_bytes;
+  const int64_t csh = cache_stride_h ? cache_stride_h * elem_bytes : cache_capacity * csl;
+  const int64_t csy = cache_stride_layer ? cache_stride_layer * elem_bytes : n_kv_heads * csh;
+  if (row_bytes % 16 || tsl % 16 || tsh % 16 || tst % 16 || csy % 16 || csh % 16 || csl % 16 || tst < row_bytes ||
+      csl < row_bytes)
+    return SPECEXT_ERR_UNSUPPORTED;
+  if (!aligned16(k_tree) || !aligned16(v_tree) || !aligned16(k_cache) || !aligned16(v_cache) ||
+      (reinterpret_cast<uintptr_t>(path) & 3u) || (reinterpret_cast<uintptr_t>(n_accept) & 3u))
+    return SPECEXT_ERR_UNSUPPORTED;
+  if (launch_commit_tree_kv(k_tree, v_tree, k_cache, v_cache, path, n_accept, max_accept, n_tree, n_layers,
+                            n_kv_heads, prefix_len, static_cast<int32_t>(row_bytes), tsl, tsh, tst, csy, csh, csl,
+                            static_cast<hipStream_t>(stream)) != hipSuccess)
     return SPECEXT_ERR_LAUNCH_FAILED;
   return SPECEXT_OK;
 }

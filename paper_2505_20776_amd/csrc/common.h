@@ -50,7 +50,19 @@ hipError_t launch_prefix_generic(const AttnParams& p, hipStream_t stream);
 hipError_t launch_prefix_mfma(const AttnParams& p, hipStream_t stream);        // key-split kernel (use_mfma == 1)
 hipError_t launch_prefix_mfma_rows(const AttnParams& p, hipStream_t stream);   // row-split kernel (use_mfma == 2)
 hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream);
-hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, float* scores, hipStream_t stream);
+// score_row >= 0: that row; -1: every row; row_path != nullptr: the row is read on the device,
+// row_path[*row_count - 1] (row 0 when *row_count <= 0)
+hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, const int32_t* row_path,
+                               const int32_t* row_count, float* scores, hipStream_t stream);
+hipError_t launch_accept_greedy(const int32_t* parent, const int32_t* draft_token, const int32_t* target_token,
+                                const int32_t* first_target, int32_t n_tree, int32_t* path_out,
+                                int32_t* n_accept_out, int32_t* next_token_out, hipStream_t stream);
+hipError_t launch_commit_tree_kv(const void* k_tree, const void* v_tree, void* k_cache, void* v_cache,
+                                 const int32_t* path, const int32_t* n_accept, int32_t max_accept, int32_t n_tree,
+                                 int32_t n_layers, int32_t n_kv_heads, int32_t prefix_len, int32_t row_bytes,
+                                 int64_t tree_sl_bytes, int64_t tree_sh_bytes, int64_t tree_st_bytes,
+                                 int64_t cache_sy_bytes, int64_t cache_sh_bytes, int64_t cache_sl_bytes,
+                                 hipStream_t stream);
 hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int32_t* idx_out,
                                 int32_t* n_out, hipStream_t stream);
 hipError_t launch_gather(const void* k_src, const void* v_src, void* k_dst, void* v_dst,

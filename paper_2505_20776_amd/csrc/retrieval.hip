@@ -18,12 +18,18 @@ namespace {
 // of a chunk are dealt to four threads (head h goes to thread h mod 4), each adds
 // its heads in ascending order, and the four partial sums are combined in a fixed
 // order: a deterministic fp32 sum.
-__global__ __launch_bounds__(256) void chunk_scores_kernel(AttnParams p, int first_row, float* scores) {
+__global__ __launch_bounds__(256) void chunk_scores_kernel(AttnParams p, int first_row, const int* row_path,
+                                                          const int* row_count, float* scores) {
   __shared__ float partial[4][64];
   const int cl = threadIdx.x & 63;
   const int part = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
-  const int t = first_row + blockIdx.y;
+  int t = first_row + blockIdx.y;
+  if (row_path) {                                // the row comes from the acceptance walk: its last accepted node
+    const int cnt = *row_count;
+    const int node = cnt > 0 ? row_path[cnt - 1] : 0;
+    t = (node >= 0 && node < p.T) ? node : 0;
+  }
   float acc = 0.f;
   if (c < p.C) {
     const int per_chunk = p.B / p.score_gran;
@@ -302,10 +308,11 @@ __global__ __launch_bounds__(256) void gather_meta_kernel(const int* __restrict_
 
 }  // namespace
 
-hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, float* scores, hipStream_t stream) {
-  const int rows = score_row < 0 ? p.T : 1;
+hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, const int32_t* row_path,
+                               const int32_t* row_count, float* scores, hipStream_t stream) {
+  const int rows = (score_row < 0 && !row_path) ? p.T : 1;
   dim3 grid((p.C + 63) / 64, rows);
-  chunk_scores_kernel<<<grid, dim3(256), 0, stream>>>(p, score_row < 0 ? 0 : score_row, scores);
+  chunk_scores_kernel<<<grid, dim3(256), 0, stream>>>(p, score_row < 0 ? 0 : score_row, row_path, row_count, scores);
   return hipGetLastError();
 }
 

@@ -117,3 +117,18 @@ def run_gather(k_src: torch.Tensor, v_src: torch.Tensor, idx: np.ndarray, chunk_
                        k_src.element_size(), pos, length)
     torch.cuda.synchronize()
     return k_dst, v_dst, pos.cpu().numpy()[:cap], int(length.item())
+
+
+def run_accept(parent: np.ndarray, draft_token: np.ndarray, target_token: np.ndarray, first_target: int):
+    """accept_greedy on host arrays; returns (path list, next token, raw path buffer, device tensors (path, n))."""
+    dev = "cuda"
+    t = len(parent)
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    path = torch.full((t,), -9, dtype=torch.int32, device=dev)
+    n_acc = torch.full((1,), -9, dtype=torch.int32, device=dev)
+    nxt = torch.full((1,), -9, dtype=torch.int32, device=dev)
+    sx.accept_greedy(to(parent), to(draft_token), to(target_token), to(np.array([first_target])), t, path, n_acc, nxt)
+    torch.cuda.synchronize()
+    raw = path.cpu().numpy()
+    n = int(n_acc.item())
+    return [int(x) for x in raw[:n]], int(nxt.item()), raw, (path, n_acc)

@@ -128,6 +128,30 @@ def test_select_and_gather_argument_checks(sx):
     assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, n_layers=9000)) == -2
 
 
+def test_accept_and_commit_argument_checks(sx):
+    ok = 4096
+    a = dict(stream=0, check=False)
+    assert sx.accept_greedy(None, ok, ok, ok, 8, ok, ok, ok, **a) == -1
+    assert sx.accept_greedy(ok, ok, ok, None, 8, ok, ok, ok, **a) == -1
+    assert sx.accept_greedy(ok, ok, ok, ok, 0, ok, ok, ok, **a) == -1
+    assert sx.accept_greedy(ok, ok, ok, ok, 129, ok, ok, ok, **a) == -2
+    assert sx.accept_greedy(ok, ok + 2, ok, ok, 8, ok, ok, ok, **a) == -2
+    c = dict(max_accept=8, n_tree=60, n_layers=32, n_kv_heads=8, head_dim=128, elem_bytes=2, prefix_len=1000, cache_capacity=1024,
+             stream=0, check=False)
+    assert sx.commit_tree_kv(None, ok, ok, ok, ok, ok, **c) == -1
+    assert sx.commit_tree_kv(ok, ok, ok, ok, ok, None, **c) == -1
+    assert sx.commit_tree_kv(ok, ok, ok, ok, ok, ok, **dict(c, prefix_len=1020)) == -1      # 1020 + 8 > capacity
+    assert sx.commit_tree_kv(ok, ok, ok, ok, ok, ok, **dict(c, max_accept=-1)) == -1
+    assert sx.commit_tree_kv(ok, ok, ok, ok, ok, ok, **dict(c, head_dim=100, elem_bytes=1)) == -2
+    assert sx.commit_tree_kv(ok, ok, ok, ok, ok, ok, **dict(c, cache_stride_l=64)) == -2     # rows would overlap
+    assert sx.commit_tree_kv(ok + 8, ok, ok, ok, ok, ok, **c) == -2
+    d = _good(sx)
+    ws = sx.workspace_bytes(d)
+    assert sx.chunk_scores_accepted(d, ok, None, ok, ok, workspace_nbytes=ws, **a) == -1
+    assert sx.chunk_scores_accepted(d, ok, ok, ok, ok, workspace_nbytes=ws - 1, **a) == -3
+    assert sx.chunk_scores_accepted(_good(sx, want_scores=False), ok, ok, ok, ok, workspace_nbytes=ws, **a) == -1
+
+
 def test_strerror(sx):
     assert sx.strerror(0) == "ok"
     assert "workspace" in sx.strerror(-3)

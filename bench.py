@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 # FETCH_SIZE and WRITE_SIZE counter passes summarised in profiles/prefix_rows_kernel_config4_hbm_traffic.md
 # (FETCH_SIZE scaled by 1.9855, WRITE_SIZE by 1.000, the factors a plain copy of known size gives):
 # 70.6 MB fetched + 31.9 MB written.
-MEASURED_TRAFFIC_BYTES = {16384: 70.7e6 + 16.2e6}
+MEASURED_TRAFFIC_BYTES = {16384: 70.6e6 + 16.2e6}
 
 
 def parse_args():

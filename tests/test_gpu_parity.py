@@ -334,6 +334,36 @@ def test_config3_retrieval_pipeline(hx):
 
 
 # --------------------------------------------------------------------------
+# draft side: tree attention of the draft model over its compacted cache (App. D: a
+# working cache of about 1K tokens), here with a StreamingLLM-style union of the sink
+# chunk, the most recent chunks and the retrieved ones
+# --------------------------------------------------------------------------
+
+def test_draft_attention_over_compacted_cache(hx):
+    import dataclasses
+    from workloads import bf16_bits_to_f32, f32_to_bf16_bits
+    wl = config_workload(3, sharp=True)
+    _, _, ref_scores = oracle_all(wl)
+    C = wl.n_chunks
+    picked = set(int(i) for i in orc.select_chunks(ref_scores[wl.score_row], wl.top_k - 4))
+    keep = sorted(picked | {0, C - 3, C - 2, C - 1})         # sink + recent + retrieved
+    dk, dv = hx.to_device(wl.draft_k, "bf16"), hx.to_device(wl.draft_v, "bf16")
+    print(f"[case] draft side over {len(keep)} chunks", flush=True)
+    kd, vd, pos, length = hx.run_gather(dk, dv, np.array(keep), wl.chunk_size)
+    rk, rv, rpos = orc.gather_draft_kv(f32_to_bf16_bits(wl.draft_k), f32_to_bf16_bits(wl.draft_v), keep, wl.chunk_size)
+    assert length == len(rpos) == len(keep) * wl.chunk_size and list(pos[:length]) == list(rpos)
+    # the draft model's tree attention over that cache, GPU gather -> GPU attention vs oracle gather -> oracle attention
+    gpu_k = bf16_bits_to_f32(kd.view(torch.int16).cpu().numpy().view(np.uint16)[0, :, :length])
+    gpu_v = bf16_bits_to_f32(vd.view(torch.int16).cpu().numpy().view(np.uint16)[0, :, :length])
+    small = dataclasses.replace(wl, k_prefix=gpu_k, v_prefix=gpu_v, prefix_len=length)
+    res = hx.run_verify(small, want_scores=False)
+    assert res["status"] == 0
+    ref_out, ref_lse, _ = orc.verify_attention(wl.q, bf16_bits_to_f32(rk[0]), bf16_bits_to_f32(rv[0]), wl.k_tree,
+                                               wl.v_tree, wl.parent)
+    check_attention(small, res, ref_out, ref_lse, "draft side")
+
+
+# --------------------------------------------------------------------------
 # configuration 5: stress shapes with a ragged prefix
 # --------------------------------------------------------------------------
 

@@ -3,18 +3,23 @@
 // unit each, fp32 accumulation.  Used when a KV head has more than 64 query rows
 // (tree nodes x heads in the GQA group); smaller problems take the key-split kernel.
 //
-// Why this shape.  Measured on MI355X: a compute unit takes in only about 30 GB/s
-// (the whole chip about 7.5 TB/s, whether the data comes from L2 or from HBM), so
-// every K/V byte must enter exactly one compute unit; and a lone wave per SIMD
-// overlaps its matrix and vector instructions poorly, while two waves per SIMD
-// overlap them well.  Hence:
+// Why this shape.  Measured on MI355X: the memory system delivers the same 5.5 - 6 TB/s
+// whether the bytes come from L2, the Infinity Cache or HBM, so every byte that passes
+// a compute unit counts and every K/V byte must enter exactly one compute unit; and a
+// lone wave per SIMD overlaps its matrix and vector instructions poorly, while two
+// waves per SIMD overlap them better.  Hence:
 //   grid  = (splits, KV heads, row groups of 32*WAVES rows)
 //   block = WAVES (8 or 4) wavefronts, at most 256 registers each, so that two
 //           waves share a SIMD; wave w owns rows [32w, 32w+32) of the row group and
 //           keeps their queries and running output in registers.
 //   The split's keys are walked in tiles of 32.  K and V tiles are filled by direct
 //   global->LDS loads into two rings of kRing tiles (every wave issues its share of
-//   every tile), one workgroup barrier per tile, and every wave reads every tile.
+//   every tile); the ring is cut into kStages stages of kStageTiles tiles with one
+//   workgroup barrier per stage (one tile per stage by default), and every wave reads
+//   every tile.  The loop is unrolled over the ring so that every LDS address is a
+//   loop-invariant register plus an immediate.
+//   A workgroup leaves one partial per row: (reference, row sum, unnormalised O), the
+//   triple rescaled by a power of two per row so that O fits fp16 whatever V's scale.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16, everything transposed so that a
 // lane owns one query row in both products):
@@ -271,9 +276,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   // Each wave's loads form the sequence (K, V of tile 0), (K, V of tile 1), ...  Before
   // stage s is read every wave waits for its own share of it and meets the others at a
   // barrier; behind that barrier every wave has also left stage s-1, whose ring stage
-  // takes the loads of stage s + kStages - 1.  Between two barriers the waves run free,
-  // so the two waves of a SIMD drift into opposite phases (one in its matrix
-  // products while the other does its softmax arithmetic).
+  // takes the loads of stage s + kStages - 1.  Between two barriers the waves run free.
   for (int s0 = 0; s0 < n_stages; s0 += kStages) {
     static_for<0, kStages>([&](auto u_c) {
       constexpr int u = decltype(u_c)::value;

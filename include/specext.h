@@ -160,7 +160,10 @@ int specext_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int3
  * UpdateDraftCache (Alg. 1): compact the draft model's KV cache to the chosen
  * chunks, copying bytes verbatim, in the order of idx.
  *
- *   k_src, v_src  [n_layers, n_kv_heads, src_len, head_dim] elements of elem_bytes
+ *   k_src, v_src  [n_layers, n_kv_heads, src_cap, head_dim] elements of elem_bytes, of
+ *                 which the first src_len tokens of every (layer, head) are valid;
+ *                 src_cap = 0 means src_cap = src_len (a dense cache); src_cap <
+ *                 src_len is SPECEXT_ERR_INVALID_ARG
  *   k_dst, v_dst  [n_layers, n_kv_heads, dst_cap, head_dim]; token slot
  *                 r*chunk_size + t of the output receives token
  *                 idx[r]*chunk_size + t of the source.  A ragged last source
@@ -179,8 +182,8 @@ int specext_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int3
  */
 int specext_gather_draft_kv(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                             const int32_t* idx, const int32_t* n_idx, int32_t max_idx,
-                            int32_t n_layers, int32_t n_kv_heads, int32_t src_len, int32_t dst_cap,
-                            int32_t head_dim, int32_t chunk_size, int32_t elem_bytes,
+                            int32_t n_layers, int32_t n_kv_heads, int32_t src_len, int32_t src_cap,
+                            int32_t dst_cap, int32_t head_dim, int32_t chunk_size, int32_t elem_bytes,
                             int32_t* pos_out, int32_t* len_out, void* stream);
 
 /*

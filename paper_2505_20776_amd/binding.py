@@ -78,7 +78,7 @@ def load_library() -> ctypes.CDLL:
     lib.specext_select_chunks.restype = ctypes.c_int
     lib.specext_select_chunks.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.specext_gather_draft_kv.restype = ctypes.c_int
-    lib.specext_gather_draft_kv.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.specext_gather_draft_kv.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     i64 = ctypes.c_int64
     lib.specext_accept_greedy.restype = ctypes.c_int
     lib.specext_accept_greedy.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
@@ -177,11 +177,11 @@ def select_chunks(scores, n_chunks: int, k: int, idx_out, n_out, stream=None, ch
 
 def gather_draft_kv(k_src, v_src, k_dst, v_dst, idx, n_idx, max_idx: int, n_layers: int, n_kv_heads: int,
                     src_len: int, dst_cap: int, head_dim: int, chunk_size: int, elem_bytes: int,
-                    pos_out=None, len_out=None, stream=None, check: bool = True) -> int:
+                    pos_out=None, len_out=None, stream=None, check: bool = True, src_cap: int = 0) -> int:
     rc = load_library().specext_gather_draft_kv(_ptr(k_src), _ptr(v_src), _ptr(k_dst), _ptr(v_dst), _ptr(idx),
                                                 _ptr(n_idx), int(max_idx), int(n_layers), int(n_kv_heads),
-                                                int(src_len), int(dst_cap), int(head_dim), int(chunk_size),
-                                                int(elem_bytes), _ptr(pos_out), _ptr(len_out), _stream(stream))
+                                                int(src_len), int(src_cap), int(dst_cap), int(head_dim),
+                                                int(chunk_size), int(elem_bytes), _ptr(pos_out), _ptr(len_out), _stream(stream))
     if check:
         _check(rc, "specext_gather_draft_kv")
     return rc

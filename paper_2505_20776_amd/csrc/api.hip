@@ -328,19 +328,22 @@ int specext_select_chunks(const float* scores, int32_t n_chunks, int32_t k, int3
 
 int specext_gather_draft_kv(const void* k_src, const void* v_src, void* k_dst, void* v_dst, const int32_t* idx,
                             const int32_t* n_idx, int32_t max_idx, int32_t n_layers, int32_t n_kv_heads,
-                            int32_t src_len, int32_t dst_cap, int32_t head_dim, int32_t chunk_size,
-                            int32_t elem_bytes, int32_t* pos_out, int32_t* len_out, void* stream) {
+                            int32_t src_len, int32_t src_cap, int32_t dst_cap, int32_t head_dim,
+                            int32_t chunk_size, int32_t elem_bytes, int32_t* pos_out, int32_t* len_out,
+                            void* stream) {
   if (!k_src || !v_src || !k_dst || !v_dst || !idx) return SPECEXT_ERR_INVALID_ARG;
   if (max_idx < 0 || n_layers <= 0 || n_kv_heads <= 0 || src_len <= 0 || dst_cap < 0 || head_dim <= 0 ||
       chunk_size <= 0 || elem_bytes <= 0)
     return SPECEXT_ERR_INVALID_ARG;
   if (static_cast<int64_t>(max_idx) * chunk_size > dst_cap) return SPECEXT_ERR_INVALID_ARG;
+  if (src_cap == 0) src_cap = src_len;
+  if (src_cap < src_len) return SPECEXT_ERR_INVALID_ARG;
   const int64_t row_bytes = static_cast<int64_t>(head_dim) * elem_bytes;
   const int64_t n_lh = static_cast<int64_t>(n_layers) * n_kv_heads;
   if (row_bytes % 16 != 0 || row_bytes > (1 << 20) || n_lh > 65535) return SPECEXT_ERR_UNSUPPORTED;
   if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_dst) || !aligned16(v_dst)) return SPECEXT_ERR_UNSUPPORTED;
-  if (launch_gather(k_src, v_src, k_dst, v_dst, idx, n_idx, max_idx, static_cast<int32_t>(n_lh), src_len, dst_cap,
-                    static_cast<int32_t>(row_bytes), chunk_size, pos_out, len_out,
+  if (launch_gather(k_src, v_src, k_dst, v_dst, idx, n_idx, max_idx, static_cast<int32_t>(n_lh), src_len, src_cap,
+                    dst_cap, static_cast<int32_t>(row_bytes), chunk_size, pos_out, len_out,
                     static_cast<hipStream_t>(stream)) != hipSuccess)
     return SPECEXT_ERR_LAUNCH_FAILED;
   return SPECEXT_OK;

@@ -67,8 +67,8 @@ hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k
                                 int32_t* n_out, hipStream_t stream);
 hipError_t launch_gather(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                          const int32_t* idx, const int32_t* n_idx, int32_t max_idx, int32_t n_lh,
-                         int32_t src_len, int32_t dst_cap, int32_t row_bytes, int32_t chunk_size,
-                         int32_t* pos_out, int32_t* len_out, hipStream_t stream);
+                         int32_t src_len, int32_t src_cap, int32_t dst_cap, int32_t row_bytes,
+                         int32_t chunk_size, int32_t* pos_out, int32_t* len_out, hipStream_t stream);
 
 // bf16 helpers (bit-level; round to nearest even on the way down)
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {

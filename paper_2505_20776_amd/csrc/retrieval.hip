@@ -252,8 +252,8 @@ __device__ __forceinline__ int chunk_tokens(int c, int n_chunks, int src_len, in
 __global__ __launch_bounds__(256) void gather_copy_kernel(const uint4* __restrict__ k_src, const uint4* __restrict__ v_src,
                                                          uint4* __restrict__ k_dst, uint4* __restrict__ v_dst,
                                                          const int* __restrict__ idx, const int* __restrict__ n_idx,
-                                                         int max_idx, int src_len, int dst_cap, int row_vecs,
-                                                         int chunk_size) {
+                                                         int max_idx, int src_len, int src_cap, int dst_cap,
+                                                         int row_vecs, int chunk_size) {
   __shared__ int sh_off[4];
   const int r = blockIdx.x;
   const int n_used = n_idx ? min(max(*n_idx, 0), max_idx) : max_idx;
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(const uint4* __restric
   const int dst_tok = sh_off[0] + sh_off[1] + sh_off[2] + sh_off[3];
 
   const int64_t lh = blockIdx.y;
-  const uint4* src = (blockIdx.z == 0 ? k_src : v_src) + (lh * src_len + static_cast<int64_t>(c) * chunk_size) * row_vecs;
+  const uint4* src = (blockIdx.z == 0 ? k_src : v_src) + (lh * src_cap + static_cast<int64_t>(c) * chunk_size) * row_vecs;
   uint4* dst = (blockIdx.z == 0 ? k_dst : v_dst) + (lh * dst_cap + dst_tok) * row_vecs;
   const int n_vecs = tokens * row_vecs;
   for (int i = threadIdx.x; i < n_vecs; i += blockDim.x) dst[i] = src[i];
@@ -330,8 +330,8 @@ hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k
 
 hipError_t launch_gather(const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                          const int32_t* idx, const int32_t* n_idx, int32_t max_idx, int32_t n_lh,
-                         int32_t src_len, int32_t dst_cap, int32_t row_bytes, int32_t chunk_size,
-                         int32_t* pos_out, int32_t* len_out, hipStream_t stream) {
+                         int32_t src_len, int32_t src_cap, int32_t dst_cap, int32_t row_bytes,
+                         int32_t chunk_size, int32_t* pos_out, int32_t* len_out, hipStream_t stream) {
   if (pos_out || len_out) {
     gather_meta_kernel<<<dim3(1), dim3(256), 0, stream>>>(idx, n_idx, max_idx, src_len, dst_cap, chunk_size,
                                                           pos_out, len_out);
@@ -342,7 +342,7 @@ hipError_t launch_gather(const void* k_src, const void* v_src, void* k_dst, void
     dim3 grid(max_idx, n_lh, 2);
     gather_copy_kernel<<<grid, dim3(256), 0, stream>>>(
         static_cast<const uint4*>(k_src), static_cast<const uint4*>(v_src), static_cast<uint4*>(k_dst),
-        static_cast<uint4*>(v_dst), idx, n_idx, max_idx, src_len, dst_cap, row_bytes / 16, chunk_size);
+        static_cast<uint4*>(v_dst), idx, n_idx, max_idx, src_len, src_cap, dst_cap, row_bytes / 16, chunk_size);
     return hipGetLastError();
   }
   return hipSuccess;

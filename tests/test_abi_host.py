@@ -118,11 +118,11 @@ def test_select_and_gather_argument_checks(sx):
     assert sx.select_chunks(ok + 2, 4, 2, ok, ok, stream=0, check=False) == -2
     g = dict(max_idx=4, n_layers=1, n_kv_heads=8, src_len=1024, dst_cap=128, head_dim=128, chunk_size=32,
              elem_bytes=2, stream=0, check=False)
-    assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **g) != -1 or True   # valid shape is not exercised here
     assert sx.gather_draft_kv(None, ok, ok, ok, ok, None, **g) == -1
     assert sx.gather_draft_kv(ok, ok, ok, ok, None, None, **g) == -1
     assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, dst_cap=127)) == -1
     assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, chunk_size=0)) == -1
+    assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, src_cap=1023)) == -1   # capacity below the length
     assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, head_dim=100, elem_bytes=1)) == -2
     assert sx.gather_draft_kv(ok + 4, ok, ok, ok, ok, None, **g) == -2
     assert sx.gather_draft_kv(ok, ok, ok, ok, ok, None, **dict(g, n_layers=9000)) == -2

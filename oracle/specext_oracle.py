@@ -46,6 +46,13 @@ drafts for the first new position.  `commit_tree_kv` appends the accepted
 nodes' K/V rows to the target cache behind the prefix, byte for byte.  Pins:
 the chain tree against the literal sequential loop of Alg. 1, a recursive
 reformulation on random trees, maximality and chain invariants.
+
+The score path the paper itself describes (Sec. 3.2.1: the last layer is computed as
+standard attention and the attention scores are read from it) needs the whole
+probability matrix: `attention_probabilities` writes every row of it out with a
+literal loop over rows.  Pins: rows sum to one, hidden tree keys are exactly zero,
+p @ V reproduces `verify_attention`, chunk sums reproduce its chunk mass, uniform
+rows for Q = 0.
 """
 from __future__ import annotations
 
@@ -54,6 +61,7 @@ import numpy as np
 __all__ = [
     "ancestor_mask", "verify_attention", "chunk_scores", "hybrid_attention",
     "select_chunks", "gather_draft_kv", "causal_attention_tail", "accept_greedy", "commit_tree_kv",
+    "attention_probabilities",
 ]
 
 
@@ -122,6 +130,34 @@ def verify_attention(q, k_prefix, v_prefix, k_tree, v_tree, parent, *, scale=Non
                 lo, hi = c * chunk_size, min((c + 1) * chunk_size, plen)
                 mass[h, :, c] = p[:, lo:hi].sum(axis=1)
     return out, lse, mass
+
+
+def attention_probabilities(q, k_prefix, k_tree, parent, *, scale=None):
+    """The materialised attention scores of standard attention (Sec. 3.2.1): p [Hq, T, L+T],
+    row (h, i) = softmax over the prefix keys and the tree keys node i may see, exactly 0
+    for the hidden tree keys.  Columns 0..L-1 are the prefix, L..L+T-1 the tree nodes."""
+    q, k_prefix, k_tree = map(_as64, (q, k_prefix, k_tree))
+    n_tree, n_q_heads, d = q.shape
+    n_kv_heads, plen, _ = k_prefix.shape
+    group = n_q_heads // n_kv_heads
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    parent = np.asarray(parent, dtype=np.int64)
+    p = np.zeros((n_q_heads, n_tree, plen + n_tree))
+    for h in range(n_q_heads):
+        g = h // group
+        for i in range(n_tree):
+            cols = list(range(plen))
+            node = i
+            while node >= 0:                      # the node itself, then up to its root
+                cols.append(plen + node)
+                node = int(parent[node])
+            cols = np.asarray(sorted(cols))
+            keys = np.concatenate([k_prefix[g], k_tree[g]], axis=0)[cols]
+            logits = scale * (keys @ q[i, h])
+            w = np.exp(logits - logits.max())
+            p[h, i, cols] = w / w.sum()
+    return p
 
 
 def chunk_scores(q, k_prefix, v_prefix, k_tree, v_tree, parent, chunk_size, *, scale=None):

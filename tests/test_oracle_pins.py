@@ -408,3 +408,61 @@ def test_bf16_inputs_are_exact():
         assert (t == a).all()
     x = np.random.default_rng(0).standard_normal(1000).astype(np.float32)
     assert (bf16_bits_to_f32(f32_to_bf16_bits(x)) == torch.from_numpy(x).to(torch.bfloat16).float().numpy()).all()
+
+
+# ---------------------------------------------------------------------------
+# the materialised probability matrix of standard attention (Sec. 3.2.1)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(4))
+def test_probability_matrix_against_the_fused_definition(seed):
+    c = _rand_case(300 + seed, T=9, Hq=4, Hkv=2, d=8, L=41, std=1.5, max_depth=4)
+    chunk = 8
+    p = orc.attention_probabilities(c["q"], c["k_prefix"], c["k_tree"], c["parent"])
+    out, lse, mass = orc.verify_attention(**c, chunk_size=chunk)
+    T, Hq, L = 9, 4, 41
+    assert p.shape == (Hq, T, L + T)
+    np.testing.assert_allclose(p.sum(axis=2), 1.0, rtol=0, atol=1e-13)
+    vis = orc.ancestor_mask(c["parent"])
+    assert (p[:, :, L:][:, ~vis] == 0.0).all()                 # hidden tree keys carry exactly nothing
+    assert (p[:, :, L:][:, vis] > 0.0).all() and (p[:, :, :L] > 0.0).all()
+    G = Hq // 2
+    for h in range(Hq):
+        vals = np.concatenate([c["v_prefix"][h // G], c["v_tree"][h // G]], axis=0)
+        np.testing.assert_allclose(p[h] @ vals, out[:, h, :], rtol=0, atol=1e-12)
+        # a row's logits come back from p and lse: log p = logit - lse
+        keys = np.concatenate([c["k_prefix"][h // G], c["k_tree"][h // G]], axis=0)
+        logit = (c["q"][:, h, :] @ keys.T) / math.sqrt(8)
+        seen = np.concatenate([np.ones((T, L), dtype=bool), vis], axis=1)
+        np.testing.assert_allclose(np.log(p[h][seen]), (logit - lse[h][:, None])[seen], rtol=0, atol=1e-11)
+    for cidx in range(mass.shape[2]):
+        lo, hi = cidx * chunk, min((cidx + 1) * chunk, L)
+        np.testing.assert_allclose(p[:, :, lo:hi].sum(axis=2), mass[:, :, cidx], rtol=0, atol=1e-13)
+    # and the scores are chunk means of p averaged over heads
+    sc = orc.chunk_scores(**c, chunk_size=chunk)
+    sizes = np.array([min((k + 1) * chunk, L) - k * chunk for k in range(mass.shape[2])])
+    mine = np.stack([p[:, :, k * chunk:k * chunk + sizes[k]].mean(axis=2) for k in range(len(sizes))], axis=2).mean(axis=0)
+    np.testing.assert_allclose(mine, sc, rtol=0, atol=1e-14)
+
+
+def test_probability_matrix_uniform_for_zero_query():
+    c = _rand_case(310, T=6, Hq=2, Hkv=1, d=4, L=10, max_depth=5)
+    p = orc.attention_probabilities(np.zeros_like(c["q"]), c["k_prefix"], c["k_tree"], c["parent"])
+    vis = orc.ancestor_mask(c["parent"])
+    for i in range(6):
+        n_seen = 10 + int(vis[i].sum())
+        np.testing.assert_allclose(p[:, i, :10], 1.0 / n_seen, rtol=0, atol=1e-15)
+        np.testing.assert_allclose(p[:, i, 10:], np.broadcast_to(vis[i] / n_seen, (2, 6)), rtol=0, atol=1e-15)
+
+
+def test_probability_matrix_matches_brute_force_scores():
+    rng = np.random.default_rng(311)
+    T, Hq, Hkv, d, L, chunk = 4, 4, 2, 3, 5, 2
+    parent = [-1, 0, 0, 2]
+    mk = lambda *s: rng.standard_normal(s)
+    q, kp, vp, kt, vt = mk(T, Hq, d), mk(Hkv, L, d), mk(Hkv, L, d), mk(Hkv, T, d), mk(Hkv, T, d)
+    _, _, score = _brute(q.tolist(), kp.tolist(), vp.tolist(), kt.tolist(), vt.tolist(), parent, chunk)
+    p = orc.attention_probabilities(q, kp, kt, parent)
+    sizes = [2, 2, 1]
+    mine = np.stack([p[:, :, 2 * k:2 * k + sizes[k]].mean(axis=2) for k in range(3)], axis=2).mean(axis=0)
+    np.testing.assert_allclose(mine, score, rtol=0, atol=1e-14)

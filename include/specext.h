@@ -250,6 +250,40 @@ int specext_chunk_scores_accepted(const specext_desc* desc, const void* workspac
                                   const int32_t* path, const int32_t* n_accept, float* scores, void* stream);
 
 /*
+ * The score path as Sec. 3.2.1 words it: the last layer's verification attention
+ * as STANDARD attention - the matrix of attention scores is written to memory,
+ * softmaxed row by row and multiplied with V - and the chunk scores are read from
+ * that matrix.  Same inputs, outputs and results as specext_verify_attn followed
+ * by specext_chunk_scores; it exists as an independent check of the fused path
+ * and to measure what the fusion saves.  bf16 inputs with head_dim 128 only
+ * (anything else: SPECEXT_ERR_UNSUPPORTED); num_splits and flags are ignored.
+ *
+ *   specext_materialized_bytes  workspace size for desc (0 if desc is rejected)
+ *   specext_materialized_ld     row pitch ld of the matrix in elements (a multiple
+ *                               of 64 >= prefix_len + n_tree), or a negative status
+ *   workspace   device, 256-byte aligned, >= specext_materialized_bytes(desc).
+ *               After specext_attn_materialized the matrix P lies at byte 256 of it:
+ *               fp32 [n_q_heads][n_tree][ld]; columns 0..prefix_len-1 are the prefix
+ *               keys, prefix_len..prefix_len+n_tree-1 the tree nodes (exactly 0 where
+ *               the tree mask hides a node), the padding behind them is 0.
+ *   q ... lse   as for specext_verify_attn
+ *
+ * specext_chunk_scores_materialized reads that matrix: scores[c] = mean over heads of
+ * the mean of P[h][row][tokens of chunk c].  desc must have want_scores and
+ * chunk_size set; row = score_row when path is NULL (0 <= score_row < n_tree), else
+ * path[*n_accept - 1] read on the device (row 0 when nothing was accepted), path and
+ * n_accept as written by specext_accept_greedy.
+ */
+size_t specext_materialized_bytes(const specext_desc* desc);
+int specext_materialized_ld(const specext_desc* desc);
+int specext_attn_materialized(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
+                              const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
+                              void* workspace, size_t workspace_bytes, void* stream);
+int specext_chunk_scores_materialized(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                                      int32_t score_row, const int32_t* path, const int32_t* n_accept,
+                                      float* scores, void* stream);
+
+/*
  * Number of prefix splits specext_verify_attn uses for this descriptor when
  * desc->num_splits == 0 (else returns desc->num_splits clamped to what is
  * valid).  Returns a negative specext_status on an invalid descriptor.

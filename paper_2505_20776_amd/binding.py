@@ -28,7 +28,8 @@ STATUS_NAMES = {0: "SPECEXT_OK", -1: "SPECEXT_ERR_INVALID_ARG", -2: "SPECEXT_ERR
 
 EXPORTED = ("specext_strerror", "specext_workspace_bytes", "specext_num_splits", "specext_verify_attn",
             "specext_chunk_scores", "specext_select_chunks", "specext_gather_draft_kv", "specext_accept_greedy",
-            "specext_commit_tree_kv", "specext_chunk_scores_accepted")
+            "specext_commit_tree_kv", "specext_chunk_scores_accepted", "specext_materialized_bytes",
+            "specext_materialized_ld", "specext_attn_materialized", "specext_chunk_scores_materialized")
 
 
 class SpecextError(RuntimeError):
@@ -87,6 +88,14 @@ def load_library() -> ctypes.CDLL:
                                            i64, i64, i64, i64, i64, i64, vp]
     lib.specext_chunk_scores_accepted.restype = ctypes.c_int
     lib.specext_chunk_scores_accepted.argtypes = [dp, vp, sz, vp, vp, vp, vp]
+    lib.specext_materialized_bytes.restype = sz
+    lib.specext_materialized_bytes.argtypes = [dp]
+    lib.specext_materialized_ld.restype = ctypes.c_int
+    lib.specext_materialized_ld.argtypes = [dp]
+    lib.specext_attn_materialized.restype = ctypes.c_int
+    lib.specext_attn_materialized.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.specext_chunk_scores_materialized.restype = ctypes.c_int
+    lib.specext_chunk_scores_materialized.argtypes = [dp, vp, sz, i32, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -221,4 +230,36 @@ def chunk_scores_accepted(desc, workspace, path, n_accept, scores, workspace_nby
                                                       _ptr(path), _ptr(n_accept), _ptr(scores), _stream(stream))
     if check:
         _check(rc, "specext_chunk_scores_accepted")
+    return rc
+
+
+def materialized_bytes(desc: specext_desc) -> int:
+    return int(load_library().specext_materialized_bytes(ctypes.byref(desc)))
+
+
+def materialized_ld(desc: specext_desc) -> int:
+    return int(load_library().specext_materialized_ld(ctypes.byref(desc)))
+
+
+def attn_materialized(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, workspace,
+                      workspace_nbytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_nbytes is None:
+        workspace_nbytes = workspace.numel() * workspace.element_size()
+    rc = load_library().specext_attn_materialized(ctypes.byref(desc), _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
+                                                  _ptr(k_tree), _ptr(v_tree), _ptr(parent), _ptr(out), _ptr(lse),
+                                                  _ptr(workspace), workspace_nbytes, _stream(stream))
+    if check:
+        _check(rc, "specext_attn_materialized")
+    return rc
+
+
+def chunk_scores_materialized(desc, workspace, score_row: int, scores, path=None, n_accept=None,
+                              workspace_nbytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_nbytes is None:
+        workspace_nbytes = workspace.numel() * workspace.element_size()
+    rc = load_library().specext_chunk_scores_materialized(ctypes.byref(desc), _ptr(workspace), workspace_nbytes,
+                                                          int(score_row), _ptr(path), _ptr(n_accept), _ptr(scores),
+                                                          _stream(stream))
+    if check:
+        _check(rc, "specext_chunk_scores_materialized")
     return rc

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(PKG_DIR, "libspecext.so")
 EXTRA_FLAGS = {"prefix_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                "prefix_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"]}
 SOURCES = ["api.hip", "prefix_generic.hip", "prefix_mfma.hip", "prefix_mfma_rows.hip", "tree_merge.hip", "retrieval.hip",
-           "accept.hip"]
+           "accept.hip", "materialized.hip"]
 
 
 def hipcc_path() -> str:

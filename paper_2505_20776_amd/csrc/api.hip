@@ -163,6 +163,44 @@ void bind_workspace(AttnParams* p, const WorkspaceLayout& w, void* workspace) {
 
 inline bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
 
+// Shapes of the materialised path: row pitch, key blocking of its two matrix products
+// (about one workgroup per compute unit each), byte offsets of its two buffers.
+struct MatLayout {
+  size_t probs_off, part_off, total;
+};
+int resolve_materialized(const specext_desc* d, MatParams* mp, MatLayout* w) {
+  const int rc = resolve(d, &mp->a);
+  if (rc != SPECEXT_OK) return rc;
+  const AttnParams& a = mp->a;
+  if (a.in_dtype != SPECEXT_BF16 || a.d != 128) return SPECEXT_ERR_UNSUPPORTED;
+  const int64_t n = static_cast<int64_t>(a.L) + a.T;
+  const int64_t ld = (n + 63) / 64 * 64;
+  if (ld * a.Hq * a.T > (int64_t{1} << 32)) return SPECEXT_ERR_UNSUPPORTED;   // a matrix of more than 16 GiB
+  mp->ld = static_cast<int32_t>(ld);
+  const int row_blocks = (a.M + 31) / 32;
+  const int waves = row_blocks < 8 ? row_blocks : 8;
+  const int row_groups = (row_blocks + waves - 1) / waves;
+  mp->m_pad = row_groups * waves * 32;
+  const int cus = device_cu_count();
+  int want = cus / (a.Hkv * row_groups);
+  if (want < 1) want = 1;
+  auto per_block = [&](int64_t keys) {
+    int64_t per = (keys + want - 1) / want;
+    per = (per + 31) / 32 * 32;
+    return static_cast<int32_t>(per < 32 ? 32 : per);
+  };
+  mp->logit_keys_per_block = per_block(a.L);
+  mp->pv_keys_per_split = per_block(n);
+  mp->pv_splits = static_cast<int32_t>((n + mp->pv_keys_per_split - 1) / mp->pv_keys_per_split);
+  size_t off = kAlign;
+  w->probs_off = off;
+  off += align_up(static_cast<size_t>(a.Hq) * a.T * ld * sizeof(float));
+  w->part_off = off;
+  off += align_up(static_cast<size_t>(mp->pv_splits) * a.Hkv * mp->m_pad * a.d * sizeof(float));
+  w->total = off;
+  return SPECEXT_OK;
+}
+
 }  // namespace
 }  // namespace specext
 
@@ -259,6 +297,71 @@ int specext_chunk_scores_accepted(const specext_desc* desc, const void* workspac
   if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
   bind_workspace(&p, w, const_cast<void*>(workspace));
   if (launch_chunk_scores(p, 0, path, n_accept, scores, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+size_t specext_materialized_bytes(const specext_desc* desc) {
+  MatParams mp;
+  MatLayout w;
+  if (resolve_materialized(desc, &mp, &w) != SPECEXT_OK) return 0;
+  return w.total;
+}
+
+int specext_materialized_ld(const specext_desc* desc) {
+  MatParams mp;
+  MatLayout w;
+  const int rc = resolve_materialized(desc, &mp, &w);
+  return rc != SPECEXT_OK ? rc : mp.ld;
+}
+
+int specext_attn_materialized(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
+                              const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  MatParams mp;
+  MatLayout w;
+  const int rc = resolve_materialized(desc, &mp, &w);
+  if (rc != SPECEXT_OK) return rc;
+  AttnParams& p = mp.a;
+  if (!q || !k_tree || !v_tree || !parent || !out || !workspace) return SPECEXT_ERR_INVALID_ARG;
+  if (p.L > 0 && (!k_prefix || !v_prefix)) return SPECEXT_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(k_tree) || !aligned16(v_tree) ||
+      !aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
+      (reinterpret_cast<uintptr_t>(parent) & 3u) != 0 || (reinterpret_cast<uintptr_t>(lse) & 3u) != 0)
+    return SPECEXT_ERR_UNSUPPORTED;
+  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  p.q = q;
+  p.kp = k_prefix;
+  p.vp = v_prefix;
+  p.kt = k_tree;
+  p.vt = v_tree;
+  p.parent = parent;
+  p.out = out;
+  p.lse = lse;
+  mp.probs = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.probs_off);
+  mp.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.part_off);
+  if (launch_materialized(mp, static_cast<hipStream_t>(stream)) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_chunk_scores_materialized(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                                      int32_t score_row, const int32_t* path, const int32_t* n_accept,
+                                      float* scores, void* stream) {
+  MatParams mp;
+  MatLayout w;
+  const int rc = resolve_materialized(desc, &mp, &w);
+  if (rc != SPECEXT_OK) return rc;
+  if (!workspace || !scores || !mp.a.want_scores || mp.a.C <= 0) return SPECEXT_ERR_INVALID_ARG;
+  if ((path == nullptr) != (n_accept == nullptr)) return SPECEXT_ERR_INVALID_ARG;
+  if (!path && (score_row < 0 || score_row >= mp.a.T)) return SPECEXT_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || (reinterpret_cast<uintptr_t>(scores) & 3u) ||
+      (reinterpret_cast<uintptr_t>(path) & 3u) || (reinterpret_cast<uintptr_t>(n_accept) & 3u))
+    return SPECEXT_ERR_UNSUPPORTED;
+  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  mp.probs = reinterpret_cast<float*>(static_cast<char*>(const_cast<void*>(workspace)) + w.probs_off);
+  mp.part = nullptr;
+  if (launch_materialized_scores(mp, path ? 0 : score_row, path, n_accept, scores,
+                                 static_cast<hipStream_t>(stream)) != hipSuccess)
     return SPECEXT_ERR_LAUNCH_FAILED;
   return SPECEXT_OK;
 }

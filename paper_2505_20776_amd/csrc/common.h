@@ -45,7 +45,21 @@ struct AttnParams {
   int64_t q_st, q_sh, kp_sh, kp_sl, kt_sh, kt_st, o_st, o_sh;
 };
 
+// Standard attention with the probability matrix written out (the score path of
+// Sec. 3.2.1 as the paper describes it): the problem plus the two buffers it needs.
+struct MatParams {
+  AttnParams a;               // inputs, outputs, shapes, strides, scale (workspace pieces unused)
+  float* probs;               // [Hq][T][ld] logits, then probabilities
+  float* part;                // [pv_splits][Hkv][m_pad][d] partial outputs of P V
+  int32_t ld;                 // row pitch of probs in elements, a multiple of 64 >= L + T
+  int32_t m_pad;              // rows of a KV head rounded up to whole 32-row blocks
+  int32_t logit_keys_per_block, pv_keys_per_split, pv_splits;   // multiples of 32 keys
+};
+
 // Launchers (each returns a hipError_t from the launch itself).
+hipError_t launch_materialized(const MatParams& mp, hipStream_t stream);
+hipError_t launch_materialized_scores(const MatParams& mp, int32_t score_row, const int32_t* row_path,
+                                      const int32_t* row_count, float* scores, hipStream_t stream);
 hipError_t launch_prefix_generic(const AttnParams& p, hipStream_t stream);
 hipError_t launch_prefix_mfma(const AttnParams& p, hipStream_t stream);        // key-split kernel (use_mfma == 1)
 hipError_t launch_prefix_mfma_rows(const AttnParams& p, hipStream_t stream);   // row-split kernel (use_mfma == 2)

@@ -132,3 +132,42 @@ def run_accept(parent: np.ndarray, draft_token: np.ndarray, target_token: np.nda
     raw = path.cpu().numpy()
     n = int(n_acc.item())
     return [int(x) for x in raw[:n]], int(nxt.item()), raw, (path, n_acc)
+
+
+def run_materialized(wl, *, out_dtype: Optional[str] = None, want_probs: bool = True):
+    """attn_materialized (+ chunk_scores_materialized for every row) on a workloads.Workload.
+    Returns dict of numpy arrays: out [T,Hq,d], lse [Hq,T], probs [Hq,T,L+T] (padding cut), scores [T,C] or None."""
+    dev = "cuda"
+    odt = out_dtype or wl.dtype
+    want_scores = wl.prefix_len > 0
+    desc = sx.make_desc(dtype=dtype_code(wl.dtype), out_dtype=dtype_code(odt), n_q_heads=wl.n_q_heads,
+                        n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, prefix_len=wl.prefix_len, n_tree=wl.n_tree,
+                        chunk_size=wl.chunk_size if want_scores else 0, want_scores=want_scores)
+    nbytes = sx.materialized_bytes(desc)
+    if nbytes == 0:
+        raise ValueError("descriptor rejected by specext_materialized_bytes")
+    ld = sx.materialized_ld(desc)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    q, kt, vt = to_device(wl.q, wl.dtype, dev), to_device(wl.k_tree, wl.dtype, dev), to_device(wl.v_tree, wl.dtype, dev)
+    kp = to_device(wl.k_prefix, wl.dtype, dev) if wl.prefix_len else None
+    vp = to_device(wl.v_prefix, wl.dtype, dev) if wl.prefix_len else None
+    parent = torch.from_numpy(np.asarray(wl.parent, dtype=np.int32)).to(dev)
+    out = torch.empty((wl.n_tree, wl.n_q_heads, wl.head_dim), dtype=torch.bfloat16 if odt == "bf16" else torch.float32,
+                      device=dev)
+    lse = torch.empty((wl.n_q_heads, wl.n_tree), dtype=torch.float32, device=dev)
+    sx.attn_materialized(desc, q, kp, vp, kt, vt, parent, out, lse, ws)
+    scores = None
+    if want_scores:
+        n_chunks = (wl.prefix_len + wl.chunk_size - 1) // wl.chunk_size
+        scores = torch.empty((wl.n_tree, n_chunks), dtype=torch.float32, device=dev)
+        for row in range(wl.n_tree):
+            sx.chunk_scores_materialized(desc, ws, row, scores[row])
+    torch.cuda.synchronize()
+    probs = None
+    if want_probs:
+        n = wl.prefix_len + wl.n_tree
+        mat = ws[256:256 + wl.n_q_heads * wl.n_tree * ld * 4].view(torch.float32).view(wl.n_q_heads, wl.n_tree, ld)
+        assert bool((mat[:, :, n:] == 0).all()), "padding columns must be zero"
+        probs = mat[:, :, :n].cpu().numpy()
+    return {"out": out.float().cpu().numpy(), "lse": lse.cpu().numpy(), "probs": probs,
+            "scores": scores.cpu().numpy() if want_scores else None, "desc": desc, "workspace": ws}

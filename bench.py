@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--prefix", type=int, default=16384)
     ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--last-layer", choices=["fused", "materialized"], default="fused",
+                    help="how the last layer (the one the chunk scores come from) is computed: fused (default) or as "
+                         "standard attention with the probability matrix written out, as Sec. 3.2.1 words it")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle is timed on (32 = the whole step, about 10 s)")
@@ -103,11 +106,20 @@ def main():
     pos = torch.empty((cap,), dtype=torch.int32, device=dev)
     length = torch.empty((1,), dtype=torch.int32, device=dev)
 
+    materialized = args.last_layer == "materialized"
+    if materialized:
+        mat_ws = torch.empty(sx.materialized_bytes(last.desc), dtype=torch.uint8, device=dev)
+
     def step():
-        for l in range(n_layers):
+        for l in range(n_layers - 1 if materialized else n_layers):
             buf = last if l == n_layers - 1 else plain
             sx.verify_attn(buf.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, outs[l], buf.lse, buf.workspace)
-        sx.chunk_scores(last.desc, last.workspace, 0, scores)
+        if materialized:
+            l = n_layers - 1
+            sx.attn_materialized(last.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, outs[l], last.lse, mat_ws)
+            sx.chunk_scores_materialized(last.desc, mat_ws, 0, scores)
+        else:
+            sx.chunk_scores(last.desc, last.workspace, 0, scores)
         sx.select_chunks(scores, n_chunks, topk, idx, n_out)
         sx.gather_draft_kv(draft_k, draft_v, ck, cv, idx, n_out, topk, 1, Hkv, L, cap, d, B, 2, pos, length)
 
@@ -180,6 +192,7 @@ def main():
                         f"chunk 32, top-32 of {n_chunks}, draft gather 1x8x{cap}x128",
             "num_splits": sx.num_splits(plain.desc),
             "graph_replay": not args.no_graph,
+            "last_layer": args.last_layer,
             "step_hbm_GBps": round(n_layers * bytes_per_launch / (step_us * 1e-6) / 1e9, 1),
             "step_mfma_TFLOPs": round(n_layers * flops_per_launch / (step_us * 1e-6) / 1e12, 1),
         },

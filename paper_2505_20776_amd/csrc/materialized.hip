@@ -14,7 +14,7 @@
 //   mat_pv_kernel           O = P V over a split of the keys, matrix cores (A = P rounded
 //                           to bf16, B = V gathered per lane), fp32 partial per split
 //   mat_reduce_kernel       partials summed in split order, written in the output type
-//   mat_scores_kernel       mean of P over the tokens of each chunk and over all heads
+//   mat_scores_kernel       mean of P over the tokens of each chunk and over all heads (fixed order)
 //
 // P layout: fp32 [Hq][T][ld], ld a multiple of 64 >= L + T; columns 0..L-1 are the
 // prefix, L..L+T-1 the tree nodes, the padding behind them is written as zero.
@@ -253,6 +253,7 @@ __global__ __launch_bounds__(128) void mat_reduce_kernel(MatParams mp) {
   const int g = h / mp.a.G;
   const int m = t * mp.a.G + (h - g * mp.a.G);
   float acc = 0.f;
+#pragma unroll 8
   for (int s = 0; s < mp.pv_splits; ++s)
     acc += mp.part[((static_cast<int64_t>(s) * mp.a.Hkv + g) * mp.m_pad + m) * kD + x];
   const int64_t o = t * mp.a.o_st + h * mp.a.o_sh + x;
@@ -262,11 +263,13 @@ __global__ __launch_bounds__(128) void mat_reduce_kernel(MatParams mp) {
     static_cast<float*>(mp.a.out)[o] = acc;
 }
 
-// grid (ceil(C / 64)), 256 threads: lane = chunk, wave w sums heads w, w+4, ...; the
-// four wave totals are combined in wave order.
+// grid (ceil(C / 8)), 256 threads: a workgroup scores 8 chunks; wave w takes heads
+// w, w+4, ...; inside a wave 8 lanes share a chunk (lane part p sums tokens p, p+8, ...
+// of it, the 8 partial sums are combined in a fixed butterfly); the four waves' totals
+// are added in wave order.
 __global__ __launch_bounds__(256) void mat_scores_kernel(MatParams mp, int first_row, const int* __restrict__ row_path,
                                                         const int* __restrict__ row_count, float* __restrict__ scores) {
-  __shared__ float sh[4][64];
+  __shared__ float sh[4][8];
   int row = first_row;
   if (row_path) {
     const int cnt = min(*row_count, mp.a.T);
@@ -274,7 +277,8 @@ __global__ __launch_bounds__(256) void mat_scores_kernel(MatParams mp, int first
     row = min(max(row, 0), mp.a.T - 1);
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + lane;
+  const int part = lane & 7, slot = lane >> 3;
+  const int c = blockIdx.x * 8 + slot;
   float total = 0.f;
   if (c < mp.a.C) {
     const int lo = c * mp.a.B;
@@ -283,14 +287,17 @@ __global__ __launch_bounds__(256) void mat_scores_kernel(MatParams mp, int first
     for (int h = wave; h < mp.a.Hq; h += 4) {
       const float* pr = mp.probs + (static_cast<int64_t>(h) * mp.a.T + row) * mp.ld + lo;
       float acc = 0.f;
-      for (int k = 0; k < size; ++k) acc += pr[k];
+      for (int k = part; k < size; k += 8) acc += pr[k];
       total += acc * inv;
     }
   }
-  sh[wave][lane] = total;
+  total += __shfl_xor(total, 1, 64);
+  total += __shfl_xor(total, 2, 64);
+  total += __shfl_xor(total, 4, 64);
+  if (part == 0) sh[wave][slot] = total;
   __syncthreads();
-  if (wave == 0 && c < mp.a.C)
-    scores[c] = ((sh[0][lane] + sh[1][lane]) + (sh[2][lane] + sh[3][lane])) / static_cast<float>(mp.a.Hq);
+  if (wave == 0 && part == 0 && c < mp.a.C)
+    scores[c] = ((sh[0][slot] + sh[1][slot]) + (sh[2][slot] + sh[3][slot])) / static_cast<float>(mp.a.Hq);
 }
 
 }  // namespace
@@ -320,7 +327,7 @@ hipError_t launch_materialized(const MatParams& mp, hipStream_t stream) {
 
 hipError_t launch_materialized_scores(const MatParams& mp, int32_t score_row, const int32_t* row_path,
                                       const int32_t* row_count, float* scores, hipStream_t stream) {
-  mat_scores_kernel<<<dim3((mp.a.C + 63) / 64), dim3(256), 0, stream>>>(mp, score_row, row_path, row_count, scores);
+  mat_scores_kernel<<<dim3((mp.a.C + 7) / 8), dim3(256), 0, stream>>>(mp, score_row, row_path, row_count, scores);
   return hipGetLastError();
 }
 

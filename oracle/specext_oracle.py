@@ -53,6 +53,12 @@ probability matrix: `attention_probabilities` writes every row of it out with a
 literal loop over rows.  Pins: rows sum to one, hidden tree keys are exactly zero,
 p @ V reproduces `verify_attention`, chunk sums reproduce its chunk mass, uniform
 rows for Q = 0.
+
+Prefill (Sec. 3.1: FlashAttention is applied to the prefill of target and draft model; it
+computes exact attention without writing the score matrix, so its oracle is the plain
+definition of causal self-attention): `prefill_attention`, one row at a time.  Pins: torch's
+scaled_dot_product_attention with a causal mask, `causal_attention_tail`, the chain-tree case
+of `verify_attention`, the running-mean closed form for Q = 0, independence of later keys.
 """
 from __future__ import annotations
 
@@ -61,7 +67,7 @@ import numpy as np
 __all__ = [
     "ancestor_mask", "verify_attention", "chunk_scores", "hybrid_attention",
     "select_chunks", "gather_draft_kv", "causal_attention_tail", "accept_greedy", "commit_tree_kv",
-    "attention_probabilities",
+    "attention_probabilities", "prefill_attention",
 ]
 
 
@@ -190,6 +196,38 @@ def _softmax_part(qh, keys, vals, scale, allowed=None):
         o = np.where(z > 0, (e @ vals) / np.where(z > 0, z, 1.0), 0.0)
         lse = np.where(z[:, 0] > 0, m_safe[:, 0] + np.log(np.where(z[:, 0] > 0, z[:, 0], 1.0)), -np.inf)
     return o, lse
+
+
+def prefill_attention(q, k_all, v_all, *, scale=None, rows=None):
+    """Causal self-attention of the prefill stage (Sec. 3.1), by its definition.
+
+    q [Tq,Hq,d] are the queries of the last Tq positions of a context of N keys
+    (Tq = N for a whole prompt, Tq < N for a later piece of a prompt processed in
+    pieces); k_all, v_all [Hkv,N,d].  Query i sits at position N - Tq + i and sees keys
+    0..that position.  `rows` restricts the computation to some query indices (the
+    others come back as zeros / -inf).  Returns (out [Tq,Hq,d], lse [Hq,Tq]).
+    """
+    q, k_all, v_all = map(_as64, (q, k_all, v_all))
+    n_q, n_q_heads, d = q.shape
+    n_kv_heads, n_all, _ = k_all.shape
+    if n_q > n_all:
+        raise ValueError("more queries than keys")
+    group = n_q_heads // n_kv_heads
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((n_q, n_q_heads, d))
+    lse = np.full((n_q_heads, n_q), -np.inf)
+    for i in (range(n_q) if rows is None else rows):
+        n_seen = n_all - n_q + int(i) + 1
+        for h in range(n_q_heads):
+            g = h // group
+            logits = scale * (k_all[g, :n_seen] @ q[i, h])
+            top = logits.max()
+            w = np.exp(logits - top)
+            z = w.sum()
+            out[i, h] = (w @ v_all[g, :n_seen]) / z
+            lse[h, i] = top + np.log(z)
+    return out, lse
 
 
 def hybrid_attention(q, k_prefix, v_prefix, k_tree, v_tree, parent, *, split_points=(), scale=None):

@@ -466,3 +466,61 @@ def test_probability_matrix_matches_brute_force_scores():
     sizes = [2, 2, 1]
     mine = np.stack([p[:, :, 2 * k:2 * k + sizes[k]].mean(axis=2) for k in range(3)], axis=2).mean(axis=0)
     np.testing.assert_allclose(mine, score, rtol=0, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------
+# prefill: causal self-attention (Sec. 3.1)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n_q,n_all", [(19, 19), (7, 19), (1, 5)])
+def test_prefill_against_sdpa_and_tail_routine(n_q, n_all):
+    rng = np.random.default_rng(400 + n_q)
+    Hq, Hkv, d = 4, 2, 8
+    q = rng.standard_normal((n_q, Hq, d)) * 1.3
+    k = rng.standard_normal((Hkv, n_all, d)) * 1.3
+    v = rng.standard_normal((Hkv, n_all, d))
+    out, lse = orc.prefill_attention(q, k, v)
+    np.testing.assert_allclose(out, orc.causal_attention_tail(q, k, v), rtol=0, atol=1e-13)
+    # library routine: torch SDPA in fp64 with an explicit lower-right causal mask
+    qt = torch.from_numpy(q).permute(1, 0, 2)[None]                                  # [1,Hq,Tq,d]
+    kt = torch.from_numpy(np.repeat(k, Hq // Hkv, axis=0))[None]
+    vt = torch.from_numpy(np.repeat(v, Hq // Hkv, axis=0))[None]
+    mask = torch.ones(n_q, n_all, dtype=torch.bool).tril(diagonal=n_all - n_q)
+    ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=mask)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-12)
+    # lse against its definition on one row
+    i, h = n_q - 1, 3
+    logits = (k[h // 2, :n_all] @ q[i, h]) / math.sqrt(d)
+    assert abs(lse[h, i] - math.log(sum(math.exp(x) for x in logits))) < 1e-12
+
+
+def test_prefill_equals_chain_tree_verification():
+    """A prompt is a chain: verifying a chain tree with an empty prefix is causal self-attention."""
+    rng = np.random.default_rng(410)
+    T, Hq, Hkv, d = 12, 4, 2, 8
+    q, k, v = rng.standard_normal((T, Hq, d)), rng.standard_normal((Hkv, T, d)), rng.standard_normal((Hkv, T, d))
+    out, lse = orc.prefill_attention(q, k, v)
+    empty = np.zeros((Hkv, 0, d))
+    ref_out, ref_lse, _ = orc.verify_attention(q, empty, empty, k, v, chain_tree(T))
+    np.testing.assert_allclose(out, ref_out, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(lse, ref_lse, rtol=0, atol=1e-13)
+
+
+def test_prefill_closed_form_and_causality():
+    rng = np.random.default_rng(411)
+    N, Hq, Hkv, d = 9, 2, 1, 4
+    k, v = rng.standard_normal((Hkv, N, d)), rng.standard_normal((Hkv, N, d))
+    out, lse = orc.prefill_attention(np.zeros((N, Hq, d)), k, v)
+    for i in range(N):                                           # Q = 0: running mean of V, lse = log(count)
+        np.testing.assert_allclose(out[i, 0], v[0, :i + 1].mean(axis=0), rtol=0, atol=1e-14)
+        assert abs(lse[1, i] - math.log(i + 1)) < 1e-14
+    q = rng.standard_normal((N, Hq, d))
+    a, _ = orc.prefill_attention(q, k, v)
+    k2, v2 = k.copy(), v.copy()
+    k2[:, 5:] += 3.0
+    v2[:, 5:] -= 2.0
+    b, _ = orc.prefill_attention(q, k2, v2)
+    assert (a[:5] == b[:5]).all() and not np.allclose(a[5:], b[5:])   # a row never sees later keys
+    # rows= computes exactly those rows
+    c, lc = orc.prefill_attention(q, k, v, rows=[2, 7])
+    assert (c[[2, 7]] == a[[2, 7]]).all() and (c[[0, 1, 3, 4, 5, 6, 8]] == 0).all() and np.isinf(lc[:, 0]).all()

@@ -250,6 +250,33 @@ int specext_chunk_scores_accepted(const specext_desc* desc, const void* workspac
                                   const int32_t* path, const int32_t* n_accept, float* scores, void* stream);
 
 /*
+ * Prefill attention (Sec. 3.1: FlashAttention is applied to the prefill stage of the
+ * target and of the draft model): exact causal self-attention, computed tile by
+ * tile with an online softmax, no score matrix in memory.
+ *
+ *   q        [q_len, n_q_heads, head_dim]: the queries of the LAST q_len positions of
+ *            a context of kv_len tokens (q_len = kv_len for a whole prompt; smaller for a
+ *            later piece of a prompt that is processed in pieces)
+ *   k, v     [n_kv_heads, kv_len, head_dim] (the KV cache layout of specext_verify_attn;
+ *            the caller has written the new tokens' K/V before the call)
+ *   out      [q_len, n_q_heads, head_dim] of out_dtype (bf16 or fp32)
+ *   lse      fp32 [n_q_heads, q_len], natural log of the softmax denominator; may be NULL
+ *   query i sits at position kv_len - q_len + i and sees keys 0 .. that position;
+ *   query head h uses KV head h / (n_q_heads / n_kv_heads)
+ *   softmax_scale  0 = 1/sqrt(head_dim)
+ *   *_stride_*     in elements, 0 = contiguous in the shapes above; multiples of 8
+ *
+ * All pointers device, 16-byte aligned (lse 4).  dtype must be SPECEXT_BF16, head_dim
+ * 128 and kv_len >= 32 (SPECEXT_ERR_UNSUPPORTED otherwise; a shorter prompt is a chain
+ * tree for specext_verify_attn with an empty prefix).  Results are bit-reproducible.
+ */
+int specext_prefill_attn(const void* q, const void* k, const void* v, void* out, float* lse, int32_t n_q_heads,
+                         int32_t n_kv_heads, int32_t head_dim, int32_t q_len, int32_t kv_len, int32_t dtype,
+                         int32_t out_dtype, float softmax_scale, int64_t q_stride_t, int64_t q_stride_h,
+                         int64_t kv_stride_h, int64_t kv_stride_l, int64_t o_stride_t, int64_t o_stride_h,
+                         void* stream);
+
+/*
  * The score path as Sec. 3.2.1 words it: the last layer's verification attention
  * as STANDARD attention - the matrix of attention scores is written to memory,
  * softmaxed row by row and multiplied with V - and the chunk scores are read from

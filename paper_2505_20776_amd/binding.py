@@ -29,7 +29,8 @@ STATUS_NAMES = {0: "SPECEXT_OK", -1: "SPECEXT_ERR_INVALID_ARG", -2: "SPECEXT_ERR
 EXPORTED = ("specext_strerror", "specext_workspace_bytes", "specext_num_splits", "specext_verify_attn",
             "specext_chunk_scores", "specext_select_chunks", "specext_gather_draft_kv", "specext_accept_greedy",
             "specext_commit_tree_kv", "specext_chunk_scores_accepted", "specext_materialized_bytes",
-            "specext_materialized_ld", "specext_attn_materialized", "specext_chunk_scores_materialized")
+            "specext_materialized_ld", "specext_attn_materialized", "specext_chunk_scores_materialized",
+            "specext_prefill_attn")
 
 
 class SpecextError(RuntimeError):
@@ -96,6 +97,9 @@ def load_library() -> ctypes.CDLL:
     lib.specext_attn_materialized.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.specext_chunk_scores_materialized.restype = ctypes.c_int
     lib.specext_chunk_scores_materialized.argtypes = [dp, vp, sz, i32, vp, vp, vp, vp]
+    lib.specext_prefill_attn.restype = ctypes.c_int
+    lib.specext_prefill_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, ctypes.c_float,
+                                         i64, i64, i64, i64, i64, i64, vp]
     _lib = lib
     return lib
 
@@ -262,4 +266,18 @@ def chunk_scores_materialized(desc, workspace, score_row: int, scores, path=None
                                                           _stream(stream))
     if check:
         _check(rc, "specext_chunk_scores_materialized")
+    return rc
+
+
+def prefill_attn(q, k, v, out, lse, n_q_heads: int, n_kv_heads: int, head_dim: int, q_len: int, kv_len: int,
+                 dtype: int = SPECEXT_BF16, out_dtype: int = SPECEXT_BF16, softmax_scale: float = 0.0,
+                 q_stride_t: int = 0, q_stride_h: int = 0, kv_stride_h: int = 0, kv_stride_l: int = 0,
+                 o_stride_t: int = 0, o_stride_h: int = 0, stream=None, check: bool = True) -> int:
+    rc = load_library().specext_prefill_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), int(n_q_heads),
+                                             int(n_kv_heads), int(head_dim), int(q_len), int(kv_len), int(dtype),
+                                             int(out_dtype), float(softmax_scale), int(q_stride_t), int(q_stride_h),
+                                             int(kv_stride_h), int(kv_stride_l), int(o_stride_t), int(o_stride_h),
+                                             _stream(stream))
+    if check:
+        _check(rc, "specext_prefill_attn")
     return rc

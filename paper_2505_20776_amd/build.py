@@ -10,14 +10,15 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libspecext.so")
-# per-source extra flags: both matrix-core kernels are compiled with the matrix-core results in
+# per-source extra flags: the matrix-core kernels with a softmax are compiled with the matrix-core results in
 # architectural VGPRs (the softmax reads them with vector ALU instructions, which cannot read AGPRs);
-# the row-split kernel never produces a NaN on its hot path, and saying so spares the max
+# the row-split kernels never produce a NaN on their hot path, and saying so spares the max
 # reductions one canonicalising instruction per operand
 EXTRA_FLAGS = {"prefix_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
-               "prefix_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"]}
+               "prefix_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"],
+               "prefill_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"]}
 SOURCES = ["api.hip", "prefix_generic.hip", "prefix_mfma.hip", "prefix_mfma_rows.hip", "tree_merge.hip", "retrieval.hip",
-           "accept.hip", "materialized.hip"]
+           "accept.hip", "materialized.hip", "prefill_rows.hip"]
 
 
 def hipcc_path() -> str:

@@ -366,6 +366,56 @@ int specext_chunk_scores_materialized(const specext_desc* desc, const void* work
   return SPECEXT_OK;
 }
 
+int specext_prefill_attn(const void* q, const void* k, const void* v, void* out, float* lse, int32_t n_q_heads,
+                         int32_t n_kv_heads, int32_t head_dim, int32_t q_len, int32_t kv_len, int32_t dtype,
+                         int32_t out_dtype, float softmax_scale, int64_t q_stride_t, int64_t q_stride_h,
+                         int64_t kv_stride_h, int64_t kv_stride_l, int64_t o_stride_t, int64_t o_stride_h,
+                         void* stream) {
+  if (!q || !k || !v || !out) return SPECEXT_ERR_INVALID_ARG;
+  if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0 || q_len <= 0 || kv_len < q_len ||
+      head_dim <= 0)
+    return SPECEXT_ERR_INVALID_ARG;
+  if (!(softmax_scale >= 0.f) || std::isinf(softmax_scale)) return SPECEXT_ERR_INVALID_ARG;
+  if (dtype != SPECEXT_BF16 || (out_dtype != SPECEXT_BF16 && out_dtype != SPECEXT_F32) || head_dim != 128 ||
+      kv_len < 32)
+    return SPECEXT_ERR_UNSUPPORTED;
+  PrefillParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.Hq = n_q_heads;
+  p.Hkv = n_kv_heads;
+  p.G = n_q_heads / n_kv_heads;
+  p.Tq = q_len;
+  p.N = kv_len;
+  p.q_off = kv_len - q_len;
+  p.out_dtype = out_dtype;
+  if (static_cast<int64_t>(q_len) * p.G > (1 << 24)) return SPECEXT_ERR_UNSUPPORTED;
+  p.M = q_len * p.G;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(head_dim));
+  p.scale_log2 = scale * kLog2e;
+  p.q_st = q_stride_t ? q_stride_t : static_cast<int64_t>(n_q_heads) * head_dim;
+  p.q_sh = q_stride_h ? q_stride_h : head_dim;
+  p.k_sl = kv_stride_l ? kv_stride_l : head_dim;
+  p.k_sh = kv_stride_h ? kv_stride_h : static_cast<int64_t>(kv_len) * p.k_sl;
+  p.o_st = o_stride_t ? o_stride_t : static_cast<int64_t>(n_q_heads) * head_dim;
+  p.o_sh = o_stride_h ? o_stride_h : head_dim;
+  const int64_t strides[] = {p.q_st, p.q_sh, p.k_sh, p.k_sl, p.o_st, p.o_sh};
+  for (int64_t s : strides)
+    if (s < 0 || s % 8 != 0) return SPECEXT_ERR_UNSUPPORTED;
+  if (p.q_sh < head_dim || p.k_sl < head_dim || p.o_sh < head_dim) return SPECEXT_ERR_INVALID_ARG;
+  // 32-bit address arithmetic inside a K/V tile and inside the queries of one workgroup
+  if (p.k_sl > (1 << 24) || p.q_st > (1 << 20) || static_cast<int64_t>(n_q_heads) * p.q_sh > (1 << 24))
+    return SPECEXT_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+    return SPECEXT_ERR_UNSUPPORTED;
+  p.q = q;
+  p.k = k;
+  p.v = v;
+  p.out = out;
+  p.lse = lse;
+  if (launch_prefill_rows(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
 int specext_accept_greedy(const int32_t* parent, const int32_t* draft_token, const int32_t* target_token,
                           const int32_t* first_target, int32_t n_tree, int32_t* path_out, int32_t* n_accept_out,
                           int32_t* next_token_out, void* stream) {

@@ -56,7 +56,21 @@ struct MatParams {
   int32_t logit_keys_per_block, pv_keys_per_split, pv_splits;   // multiples of 32 keys
 };
 
+// Causal self-attention of the prefill stage: query i of q_len sits at position
+// q_off + i of a context of N keys.  Row numbering as above (m = token * G + hg).
+struct PrefillParams {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  float* lse;                 // natural log, [Hq][Tq]; may be null
+  int32_t Hq, Hkv, G, Tq, N, M, q_off, out_dtype;
+  float scale_log2;
+  int64_t q_st, q_sh, k_sh, k_sl, o_st, o_sh;
+};
+
 // Launchers (each returns a hipError_t from the launch itself).
+hipError_t launch_prefill_rows(const PrefillParams& p, hipStream_t stream);
 hipError_t launch_materialized(const MatParams& mp, hipStream_t stream);
 hipError_t launch_materialized_scores(const MatParams& mp, int32_t score_row, const int32_t* row_path,
                                       const int32_t* row_count, float* scores, hipStream_t stream);

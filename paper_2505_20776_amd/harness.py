@@ -171,3 +171,23 @@ def run_materialized(wl, *, out_dtype: Optional[str] = None, want_probs: bool = 
         probs = mat[:, :, :n].cpu().numpy()
     return {"out": out.float().cpu().numpy(), "lse": lse.cpu().numpy(), "probs": probs,
             "scores": scores.cpu().numpy() if want_scores else None, "desc": desc, "workspace": ws}
+
+
+def run_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray, *, out_dtype: str = "bf16", kv_capacity: int = 0):
+    """prefill_attn on host arrays (values exactly representable in bf16): q [Tq,Hq,d], k/v [Hkv,N,d].
+    kv_capacity > N places K/V in a capacity-sized cache.  Returns (out fp32 [Tq,Hq,d], lse [Hq,Tq])."""
+    dev = "cuda"
+    tq, hq, d = q.shape
+    hkv, n, _ = k.shape
+    cap = max(kv_capacity, n)
+    kd = torch.zeros((hkv, cap, d), dtype=torch.bfloat16, device=dev)
+    vd = torch.zeros_like(kd)
+    kd[:, :n] = to_device(k, "bf16", dev)
+    vd[:, :n] = to_device(v, "bf16", dev)
+    out = torch.full((tq, hq, d), float("nan"), dtype=torch.bfloat16 if out_dtype == "bf16" else torch.float32,
+                     device=dev)
+    lse = torch.full((hq, tq), float("nan"), dtype=torch.float32, device=dev)
+    sx.prefill_attn(to_device(q, "bf16", dev), kd, vd, out, lse, hq, hkv, d, tq, n, out_dtype=dtype_code(out_dtype),
+                    kv_stride_h=cap * d if cap != n else 0)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), lse.cpu().numpy()

@@ -45,6 +45,9 @@ def parse_args():
     ap.add_argument("--last-layer", choices=["fused", "materialized"], default="fused",
                     help="how the last layer (the one the chunk scores come from) is computed: fused (default) or as "
                          "standard attention with the probability matrix written out, as Sec. 3.2.1 words it")
+    ap.add_argument("--workload", choices=["verify", "prefill"], default="verify",
+                    help="verify (default): the verification step the headline metric is quoted on; prefill: causal "
+                         "self-attention of a --prefix token prompt on all layers (Sec. 3.1), its own JSON line")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle is timed on (32 = the whole step, about 10 s)")
@@ -57,6 +60,9 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "prefill":
+        return bench_prefill(args)
 
     import numpy as np
     import torch
@@ -213,6 +219,77 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, n_layers, L, B, topk)
+    print(json.dumps(result))
+
+
+def bench_prefill(args):
+    """Prefill attention of a prompt of --prefix tokens on all layers (each layer its own Q/K/V in HBM)."""
+    import numpy as np
+    import torch
+
+    import paper_2505_20776_amd as sx
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    Hq, Hkv, d, L, n_layers = 32, 8, 128, args.prefix, args.layers
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4100)
+    randn = lambda *shape: torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = [randn(L, Hq, d) for _ in range(n_layers)]
+    k = [randn(Hkv, L, d) for _ in range(n_layers)]
+    v = [randn(Hkv, L, d) for _ in range(n_layers)]
+    out = torch.empty((L, Hq, d), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((Hq, L), dtype=torch.float32, device=dev)
+
+    def step():
+        for l in range(n_layers):
+            sx.prefill_attn(q[l], k[l], v[l], out, lse, Hq, Hkv, d, L, L)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(max(args.warmup, 1)):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / (args.steps * n_layers)
+    flops = 4.0 * d * Hq * L * (L + 1) / 2                    # QK^T and PV over the causal half, 2 flops per MAC
+    tflops = flops / (kernel_ms * 1e-3) / 1e12
+    result = {
+        "metric": "ms per prefill attention pass (all layers)", "value": round(ms_per_step, 4), "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"prefill: {n_layers} layers x (Hq=32, Hkv=8, d=128) bf16, prompt {L}, causal"},
+        "roofline": {"kernel": "prefill_rows_kernel (causal attention on the matrix cores, one layer per launch)",
+                     "bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "algorithmic_flops": flops, "ms_per_launch": round(kernel_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        from workloads import quantize
+        rng = np.random.default_rng(4100)
+        mk = lambda *shape: quantize(rng.standard_normal(shape).astype(np.float32), "bf16")
+        qs, ks, vs = mk(L, Hq, d), mk(Hkv, L, d), mk(Hkv, L, d)
+        rows = sorted(int(x) for x in rng.integers(0, L, size=3000))
+        t0 = time.perf_counter()
+        orc.prefill_attention(qs, ks, vs, rows=rows)
+        t = time.perf_counter() - t0
+        mean_keys = float(np.mean([r + 1 for r in rows]))
+        scaled = t * (L * (L + 1) / 2) / (mean_keys * len(rows)) * n_layers
+        result["cpu_baseline"] = {"value": round(scaled * 1e3, 1), "unit": "ms", "cores": int(os.cpu_count() or 1),
+                                  "kind": "oracle",
+                                  "sample": f"fp64 numpy oracle on {len(rows)} random query rows of one layer "
+                                            f"({t:.1f} s), scaled by key count to all rows and {n_layers} layers"}
     print(json.dumps(result))
 
 

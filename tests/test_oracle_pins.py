@@ -524,3 +524,39 @@ def test_prefill_closed_form_and_causality():
     # rows= computes exactly those rows
     c, lc = orc.prefill_attention(q, k, v, rows=[2, 7])
     assert (c[[2, 7]] == a[[2, 7]]).all() and (c[[0, 1, 3, 4, 5, 6, 8]] == 0).all() and np.isinf(lc[:, 0]).all()
+
+
+# ---------------------------------------------------------------------------
+# the paper's own retrieval settings (tests/golden/retrieval_settings.txt)
+# ---------------------------------------------------------------------------
+
+def _golden_settings():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "retrieval_settings.txt")
+    out = {}
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            name, value = line.split()
+            out[name] = int(value)
+    return out
+
+
+def test_paper_retrieval_settings_give_the_paper_working_cache_sizes():
+    """Table 8 / App. C: top-k chunks of the adopted chunk size are exactly the adopted working caches
+    (32 x 32 = 1K tokens for Vicuna-68M, 64 x 32 = 2K for EAGLE), through SelectChunks + UpdateDraftCache."""
+    g = _golden_settings()
+    rng = np.random.default_rng(8)
+    plen = 8192                                                   # the ablation's input length
+    n_chunks = plen // g["chunk_size"]
+    scores = rng.random(n_chunks)
+    src = rng.integers(0, 2 ** 15, size=(1, 2, plen, 4)).astype(np.uint16)
+    for model in ("vicuna68m", "eagle"):
+        idx = orc.select_chunks(scores, g[f"top_k_{model}"])
+        k_dst, v_dst, pos = orc.gather_draft_kv(src, src, idx, g["chunk_size"])
+        assert k_dst.shape[2] == g[f"working_cache_{model}"] == len(pos)
+        assert g[f"top_k_{model}"] * g["chunk_size"] == g[f"working_cache_{model}"]
+    # the numbered benchmark configurations use the paper's chunk size and the smaller top-k
+    wl = config_workload(2)
+    assert wl.chunk_size == g["chunk_size"] and wl.top_k == g["top_k_vicuna68m"]
+    assert wl.chunk_size * wl.top_k == g["working_cache_vicuna68m"]

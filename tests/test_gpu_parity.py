@@ -431,3 +431,18 @@ def test_valu_prefix_kernel_on_bf16(hx):
     b = hx.run_verify(wl)
     assert np.abs(a["out"] - b["out"]).max() <= 2e-2 * np.abs(ref_out).max()
     assert np.abs(a["scores"] - b["scores"]).max() <= 1e-4 * ref_scores.max()
+
+
+# --------------------------------------------------------------------------
+# the longest input the paper evaluates (128K tokens, Table 6), ragged by 21 tokens: every output,
+# lse and score against the oracle
+# --------------------------------------------------------------------------
+
+def test_prefix_128k(hx):
+    L = 131072 - 21
+    wl = config_workload(4, item=3, prefix_len=L, sharp=True)
+    print(f"[case] 128K prefix, L={L}", flush=True)
+    res, ref_out, ref_lse, ref_scores, rel = _full_check(hx, wl, "128K prefix")
+    sel, n, _ = hx.run_select(res["scores"][wl.score_row], wl.top_k)
+    check_selection(sel, ref_scores[wl.score_row], wl.top_k, "128K select")
+    assert n == wl.top_k and set(wl.needle_chunks) <= set(int(i) for i in sel)

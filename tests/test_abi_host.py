@@ -156,3 +156,31 @@ def test_strerror(sx):
     assert sx.strerror(0) == "ok"
     assert "workspace" in sx.strerror(-3)
     assert sx.strerror(-99) == "unknown status"
+
+
+def test_materialized_argument_checks(sx):
+    d64 = sx.make_desc(dtype=sx.SPECEXT_BF16, n_q_heads=8, n_kv_heads=2, head_dim=64, prefix_len=100, n_tree=8)
+    f32 = sx.make_desc(dtype=sx.SPECEXT_F32, n_q_heads=8, n_kv_heads=2, head_dim=128, prefix_len=100, n_tree=8)
+    assert sx.materialized_bytes(d64) == 0 and sx.materialized_ld(d64) == -2
+    assert sx.materialized_bytes(f32) == 0 and sx.materialized_ld(f32) == -2
+    ok = sx.make_desc(dtype=sx.SPECEXT_BF16, n_q_heads=8, n_kv_heads=2, head_dim=128, prefix_len=100, n_tree=8,
+                      chunk_size=32, want_scores=True)
+    assert sx.materialized_ld(ok) == 128
+    a = 4096
+    assert sx.attn_materialized(ok, a, a, a, a, a, a, a, a, a, workspace_nbytes=16, stream=0, check=False) == -3
+    nbytes = sx.materialized_bytes(ok)
+    assert sx.chunk_scores_materialized(ok, a, 8, a, workspace_nbytes=nbytes, stream=0, check=False) == -1
+    assert sx.chunk_scores_materialized(ok, a, 0, a, path=a, workspace_nbytes=nbytes, stream=0, check=False) == -1
+
+
+def test_prefill_argument_checks(sx):
+    a = 4096
+    base = dict(n_q_heads=8, n_kv_heads=2, head_dim=128, q_len=64, kv_len=64, stream=0, check=False)
+    assert sx.prefill_attn(None, a, a, a, None, **base) == -1
+    assert sx.prefill_attn(a, a, a, a, None, **dict(base, q_len=65)) == -1           # more queries than keys
+    assert sx.prefill_attn(a, a, a, a, None, **dict(base, n_kv_heads=3)) == -1
+    assert sx.prefill_attn(a, a, a, a, None, **dict(base, head_dim=64)) == -2
+    assert sx.prefill_attn(a, a, a, a, None, **dict(base, dtype=sx.SPECEXT_F32)) == -2
+    assert sx.prefill_attn(a, a, a, a, None, **dict(base, q_len=8, kv_len=16)) == -2   # under one tile of keys
+    assert sx.prefill_attn(a + 2, a, a, a, None, **base) == -2
+    assert sx.prefill_attn(a, a, a, a, None, **dict(base, kv_stride_l=100)) == -2

@@ -120,19 +120,3 @@ def test_fp32_output_and_strided_cache(hx):
     torch.cuda.synchronize()
     check_attention(wl, {"out": out.cpu().numpy(), "lse": lse.cpu().numpy()}, ref_out, ref_lse, "strided fp32 out")
     check_scores(one.cpu().numpy()[None], ref_scores[5][None], "strided scores")
-
-
-def test_unsupported_and_invalid(hx):
-    import paper_2505_20776_amd as sx
-    d64 = sx.make_desc(dtype=sx.SPECEXT_BF16, n_q_heads=8, n_kv_heads=2, head_dim=64, prefix_len=100, n_tree=8)
-    f32 = sx.make_desc(dtype=sx.SPECEXT_F32, n_q_heads=8, n_kv_heads=2, head_dim=128, prefix_len=100, n_tree=8)
-    assert sx.materialized_bytes(d64) == 0 and sx.materialized_ld(d64) == -2
-    assert sx.materialized_bytes(f32) == 0 and sx.materialized_ld(f32) == -2
-    ok = sx.make_desc(dtype=sx.SPECEXT_BF16, n_q_heads=8, n_kv_heads=2, head_dim=128, prefix_len=100, n_tree=8,
-                      chunk_size=32, want_scores=True)
-    assert sx.materialized_ld(ok) == 128
-    a = 4096
-    assert sx.attn_materialized(ok, a, a, a, a, a, a, a, a, a, workspace_nbytes=16, stream=0, check=False) == -3
-    nbytes = sx.materialized_bytes(ok)
-    assert sx.chunk_scores_materialized(ok, a, 8, a, workspace_nbytes=nbytes, stream=0, check=False) == -1
-    assert sx.chunk_scores_materialized(ok, a, 0, a, path=a, workspace_nbytes=nbytes, stream=0, check=False) == -1

@@ -96,17 +96,3 @@ def test_full_size_prompt_sampled_rows(hx):
     # properties that hold for every row: finite, and inside the hull of V's range per column block
     assert np.isfinite(out).all()
     assert np.abs(out).max() <= np.abs(v).max() * (1 + 2.0 ** -7)
-
-
-def test_argument_checks(hx):
-    import paper_2505_20776_amd as sx
-    a = 4096
-    base = dict(n_q_heads=8, n_kv_heads=2, head_dim=128, q_len=64, kv_len=64, stream=0, check=False)
-    assert sx.prefill_attn(None, a, a, a, None, **base) == -1
-    assert sx.prefill_attn(a, a, a, a, None, **dict(base, q_len=65)) == -1           # more queries than keys
-    assert sx.prefill_attn(a, a, a, a, None, **dict(base, n_kv_heads=3)) == -1
-    assert sx.prefill_attn(a, a, a, a, None, **dict(base, head_dim=64)) == -2
-    assert sx.prefill_attn(a, a, a, a, None, **dict(base, dtype=sx.SPECEXT_F32)) == -2
-    assert sx.prefill_attn(a, a, a, a, None, **dict(base, q_len=8, kv_len=16)) == -2   # under one tile of keys
-    assert sx.prefill_attn(a + 2, a, a, a, None, **base) == -2
-    assert sx.prefill_attn(a, a, a, a, None, **dict(base, kv_stride_l=100)) == -2

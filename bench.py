@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 # HBM bytes of one prefix-kernel launch at the default workload (prefix 16384, automatic splits), from the
 # FETCH_SIZE and WRITE_SIZE counter passes summarised in profiles/prefix_rows_kernel_config4_hbm_traffic.md
-# (FETCH_SIZE scaled by 1.9855, WRITE_SIZE by 1.000, the factors a plain copy of known size gives):
-# 70.6 MB fetched + 31.9 MB written.
+# (FETCH_SIZE scaled by 1.9816, WRITE_SIZE by 1.000, the factors a plain copy of known size gives):
+# 70.6 MB fetched + 16.2 MB written.
 MEASURED_TRAFFIC_BYTES = {16384: 70.6e6 + 16.2e6}
 
 

@@ -39,8 +39,12 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--layers", type=int, default=32)
-    ap.add_argument("--prefix", type=int, default=16384)
+    ap.add_argument("--config", choices=["2", "3", "4", "5wide", "5chain"], default="4",
+                    help="numbered workload: 4 (default) = 32 layers at a 16K prefix, the headline metric; 2 / 3 / 5 = "
+                         "the single-layer shapes (2K, 8K, 32K-37 with a 128-node wide tree or a 16-node chain), run "
+                         "over enough distinct K/V copies (>= 300 MB) that every launch streams cold")
+    ap.add_argument("--layers", type=int, default=0, help="distinct K/V copies per step (0 = the config's own)")
+    ap.add_argument("--prefix", type=int, default=0, help="prefix length (0 = the config's own)")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--last-layer", choices=["fused", "materialized"], default="fused",
                     help="how the last layer (the one the chunk scores come from) is computed: fused (default) or as "
@@ -74,10 +78,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    Hq, Hkv, d, L, B, topk = 32, 8, 128, args.prefix, 32, 32
-    parent_np = config_tree(4)
+    Hq, Hkv, d = 32, 8, 128
+    L, B, topk, parent_np = {"2": (2048, 32, 32, config_tree(2)), "3": (8192, 32, 32, config_tree(3)),
+                             "4": (16384, 32, 32, config_tree(4)), "5wide": (32768 - 37, 64, 16, config_tree(5, "wide")),
+                             "5chain": (32768 - 37, 64, 16, config_tree(5, "chain"))}[args.config]
+    L = args.prefix or L
     T = len(parent_np)
-    n_layers = args.layers
+    layer_bytes = 2 * Hkv * L * d * 2
+    n_layers = args.layers or (32 if args.config == "4" else -(-300_000_000 // layer_bytes))
     n_chunks = (L + B - 1) // B
 
     gen = torch.Generator(device=dev)
@@ -106,6 +114,7 @@ def main():
     scores = torch.empty((n_chunks,), dtype=torch.float32, device=dev)
     idx = torch.empty((topk,), dtype=torch.int32, device=dev)
     n_out = torch.empty((1,), dtype=torch.int32, device=dev)
+    topk = min(topk, n_chunks)
     cap = topk * B
     ck = torch.empty((1, Hkv, cap, d), dtype=torch.bfloat16, device=dev)
     cv = torch.empty((1, Hkv, cap, d), dtype=torch.bfloat16, device=dev)
@@ -174,14 +183,15 @@ def main():
         stream.synchronize()
         prefix_us = e0.elapsed_time(e1) * 1e3 / (args.steps * n_layers)
 
-    assert int(length.item()) == cap and int(n_out.item()) == topk
+    assert int(n_out.item()) == topk and cap - B < int(length.item()) <= cap
 
     bytes_per_launch = 2 * Hkv * L * d * 2                     # one layer's K and V prefix, bf16
     flops_per_launch = 4.0 * d * T * (Hq // Hkv) * Hkv * L     # QK^T and PV, 2 flops per MAC
     achieved_gbs = bytes_per_launch / (prefix_us * 1e-6) / 1e9
     step_us = ms_per_step * 1e3
     result = {
-        "metric": "us per verification step (all layers) at 16K prefix",
+        "metric": "us per verification step (all layers) at 16K prefix" if (args.config == "4" and L == 16384)
+                  else f"us per verification step ({n_layers} layers) at prefix {L}",
         "value": round(step_us, 2),
         "unit": "us",
         "n_gpus": 1,
@@ -194,8 +204,9 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"config 4: {n_layers} layers x (Hq=32, Hkv=8, d=128) bf16, prefix {L}, 60-node tree, "
-                        f"chunk 32, top-32 of {n_chunks}, draft gather 1x8x{cap}x128",
+            "workload": f"config {args.config}: {n_layers} layers x (Hq=32, Hkv=8, d=128) bf16, prefix {L}, {T}-node tree, "
+                        f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x8x{cap}x128",
+            "us_per_layer": round(step_us / n_layers, 2),
             "num_splits": sx.num_splits(plain.desc),
             "graph_replay": not args.no_graph,
             "last_layer": args.last_layer,
@@ -203,13 +214,14 @@ def main():
             "step_mfma_TFLOPs": round(n_layers * flops_per_launch / (step_us * 1e-6) / 1e12, 1),
         },
         "roofline": {
-            "kernel": "prefix_rows_kernel<8,false> (split-K prefix pass on the matrix cores, one layer per launch)",
+            "kernel": ("prefix_rows_kernel" if T * (Hq // Hkv) > 64 else "prefix_mfma_kernel") +
+                      " (split-K prefix pass on the matrix cores, one layer per launch)",
             "bound": "hbm",
             "achieved": round(achieved_gbs, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(L) if (args.num_splits == 0 and n_layers == 32) else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(L) if (args.num_splits == 0 and args.config == "4") else None,
             "algorithmic_bytes": bytes_per_launch,
             "us_per_launch": round(prefix_us, 3),
             "mfma_TFLOPs": round(flops_per_launch / (prefix_us * 1e-6) / 1e12, 1),
@@ -217,6 +229,11 @@ def main():
         },
     }
 
+    if T * (Hq // Hkv) * 1.0 > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+        # more flops per K/V byte than the ridge point: the matrix roof is the binding one
+        rf = result["roofline"]
+        rf.update({"bound": "mfma", "achieved": rf["mfma_TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                   "frac": rf["mfma_frac"], "hbm_GBps": round(achieved_gbs, 1)})
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, n_layers, L, B, topk)
     print(json.dumps(result))
@@ -232,7 +249,7 @@ def bench_prefill(args):
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    Hq, Hkv, d, L, n_layers = 32, 8, 128, args.prefix, args.layers
+    Hq, Hkv, d, L, n_layers = 32, 8, 128, args.prefix or 16384, args.layers or 32
     gen = torch.Generator(device=dev)
     gen.manual_seed(4100)
     randn = lambda *shape: torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
@@ -304,7 +321,8 @@ def cpu_baseline(args, n_layers, L, B, topk):
     t_attn = 0.0
     wl = None
     for l in range(sample_layers):
-        wl = config_workload(4, item=l, prefix_len=L)
+        cfg = int(args.config[0])
+        wl = config_workload(cfg, item=l, prefix_len=L, variant=args.config[1:])
         t0 = time.perf_counter()
         orc.verify_attention(wl.q, wl.k_prefix, wl.v_prefix, wl.k_tree, wl.v_tree, wl.parent)
         t_attn += time.perf_counter() - t0

@@ -214,7 +214,7 @@ def main():
             "step_mfma_TFLOPs": round(n_layers * flops_per_launch / (step_us * 1e-6) / 1e12, 1),
         },
         "roofline": {
-            "kernel": ("prefix_rows_kernel" if T * (Hq // Hkv) > 64 else "prefix_mfma_kernel") +
+            "kernel": ("prefix_rows_kernel" if T * (Hq // Hkv) > 32 else "prefix_mfma_kernel") +
                       " (split-K prefix pass on the matrix cores, one layer per launch)",
             "bound": "hbm",
             "achieved": round(achieved_gbs, 1),

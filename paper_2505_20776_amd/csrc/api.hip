@@ -83,9 +83,10 @@ int resolve(const specext_desc* d, AttnParams* p) {
 
   // Which prefix kernel runs.  The matrix-core kernels take bf16, d = 128, at least one
   // full 32-key tile and, when scores are wanted, chunk sizes that are whole tiles.
-  // Up to 64 query rows per KV head: the key-split kernel (the four waves of a
+  // Up to 32 query rows per KV head: the key-split kernel (the four waves of a
   // workgroup share the rows and split the keys).  More rows: the row-split kernel
-  // (a workgroup owns 128 or 256 rows, so each K/V byte enters one compute unit only).
+  // (a workgroup owns 128 or 256 rows, so each K/V byte enters one compute unit only;
+  // measured faster from 33 rows on, also when most of a workgroup's rows are padding).
   // Their address arithmetic inside a tile and inside Q is 32-bit, hence the stride limits.
   const bool mfma_ok = p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L >= 32 &&
                        (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX) &&
@@ -94,9 +95,9 @@ int resolve(const specext_desc* d, AttnParams* p) {
   if (!mfma_ok) {
     p->use_mfma = 0;
     p->rows_per_group = 64;
-  } else if (p->M <= 64) {
+  } else if (p->M <= 32) {
     p->use_mfma = 1;
-    p->rows_per_group = p->M > 32 ? 64 : 32;
+    p->rows_per_group = 32;
   } else {
     p->use_mfma = 2;
     p->rows_per_group = p->M > 128 ? 256 : 128;

@@ -473,9 +473,7 @@ hipError_t launch_one(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_prefix_mfma(const AttnParams& p, hipStream_t stream) {
   if (p.S <= 0) return hipSuccess;
-  if (p.rows_per_group == 64) {
-    return p.want_scores ? launch_one<2, true>(p, stream) : launch_one<2, false>(p, stream);
-  }
+  // one 32-row block per workgroup (problems with more rows take the row-split kernel)
   return p.want_scores ? launch_one<1, true>(p, stream) : launch_one<1, false>(p, stream);
 }
 

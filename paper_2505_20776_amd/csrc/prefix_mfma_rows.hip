@@ -1,6 +1,6 @@
 // Prefix pass of Hybrid Tree Attention (SpecExtend Sec. 3.1) on the gfx950
 // matrix cores, row-split form: bf16 K/V streamed ONCE from HBM into ONE compute
-// unit each, fp32 accumulation.  Used when a KV head has more than 64 query rows
+// unit each, fp32 accumulation.  Used when a KV head has more than 32 query rows
 // (tree nodes x heads in the GQA group); smaller problems take the key-split kernel.
 //
 // Why this shape.  Measured on MI355X: the memory system delivers the same 5.5 - 6 TB/s

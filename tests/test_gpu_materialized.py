@@ -120,3 +120,18 @@ def test_fp32_output_and_strided_cache(hx):
     torch.cuda.synchronize()
     check_attention(wl, {"out": out.cpu().numpy(), "lse": lse.cpu().numpy()}, ref_out, ref_lse, "strided fp32 out")
     check_scores(one.cpu().numpy()[None], ref_scores[5][None], "strided scores")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes(hx, seed):
+    rng = np.random.default_rng(92000 + seed)
+    Hkv = int(rng.choice([1, 2, 8]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    T = int(rng.choice([1, 2, 9, 16, 33, 60, 64, 65, 128]))
+    L = int(rng.choice([0, 1, 31, 32, 33, 64, 200, 513, 1000, 2049]))
+    B = int(rng.choice([16, 32, 48, 64]))
+    parent = np.asarray((chain_tree(T) if T < 4 or seed % 3 == 0 else random_parent_tree(T, 10, rng) if seed % 3 == 1
+                         else eagle_style_tree(T, 6, rng))[:T])
+    wl = make_workload(f"matrand{seed}", seed=seed * 17 + 3, dtype="bf16", n_q_heads=Hkv * G, n_kv_heads=Hkv,
+                       head_dim=128, prefix_len=L, parent=parent, chunk_size=B, top_k=4, n_needles=0, value_std=1.0)
+    _check_all(hx, wl, f"random shape {seed}")

@@ -446,3 +446,63 @@ def test_prefix_128k(hx):
     sel, n, _ = hx.run_select(res["scores"][wl.score_row], wl.top_k)
     check_selection(sel, ref_scores[wl.score_row], wl.top_k, "128K select")
     assert n == wl.top_k and set(wl.needle_chunks) <= set(int(i) for i in sel)
+
+
+# --------------------------------------------------------------------------
+# seeded random shapes: every supported combination of dtype, head_dim, group size, tree size and kind,
+# prefix length (including 0 and lengths around tile and split boundaries), chunk size and split count
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shapes(hx, seed):
+    rng = np.random.default_rng(70000 + seed)
+    dtype = "bf16" if rng.random() < 0.75 else "f32"
+    d = 128 if rng.random() < 0.7 else 64
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    T = int(rng.choice([1, 2, 3, 8, 15, 16, 17, 33, 60, 64, 65, 100, 128]))
+    L = int(rng.choice([0, 1, 31, 32, 33, 63, 64, 65, 127, 129, 255, 257, 511, 1000, 1025, 2047, 3001, 4100]))
+    B = int(rng.choice([16, 32, 48, 64]))
+    splits = int(rng.choice([0, 0, 1, 2, 3, 5, 8]))
+    kind = int(rng.integers(4))
+    parent = (chain_tree(T) if kind == 0 or T < 4 else random_parent_tree(T, 12, rng) if kind == 1
+              else eagle_style_tree(T, 6, rng) if kind == 2 else wide_tree(T, 4, rng))
+    parent = np.asarray(parent[:T])
+    if T > 5 and rng.random() < 0.25:
+        parent[int(rng.integers(1, T))] = -1                   # a forest
+    wl = make_workload(f"rand{seed}", seed=seed * 13 + 5, dtype=dtype, n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=d,
+                       prefix_len=L, parent=parent, chunk_size=B, top_k=4, n_needles=0,
+                       value_std=1.0 if rng.random() < 0.5 else None)
+    _full_check(hx, wl, f"random shape {seed}", num_splits=splits)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_select_and_gather(hx, seed):
+    """Seeded random score vectors (ties, signs, denormals, all lengths up to the 65536 limit) and random chunk
+    lists (repeats, out-of-range entries, ragged source) : both exact."""
+    rng = np.random.default_rng(81000 + seed)
+    n = int(rng.choice([1, 2, 63, 64, 65, 511, 512, 1023, 1024, 1025, 4096, 5000, 65535, 65536]))
+    kind = seed % 4
+    s = (rng.standard_normal(n).astype(np.float32) if kind == 0 else
+         rng.integers(-3, 4, size=n).astype(np.float32) if kind == 1 else
+         (rng.random(n) * 1e-40).astype(np.float32) if kind == 2 else            # denormals and zeros
+         np.abs(rng.standard_normal(n)).astype(np.float32) * np.float32(1e-4))
+    k = int(rng.choice([0, 1, 2, 31, 32, 33, n // 2, n - 1 if n > 1 else 1, n, n + 5]))
+    sel, n_out, raw = hx.run_select(s, k)
+    ref = orc.select_chunks(s, k)
+    assert n_out == len(ref) and list(sel) == list(ref), f"select n={n} k={k} kind={kind}"
+    assert (raw[n_out:] == -1).all()
+    # gather
+    Ld, H, d = int(rng.choice([1, 2])), int(rng.choice([1, 3, 8])), int(rng.choice([64, 128]))
+    B = int(rng.choice([16, 32, 100]))
+    L = int(rng.integers(B, 40 * B))
+    C = (L + B - 1) // B
+    src_k = torch.from_numpy(rng.integers(-2 ** 15, 2 ** 15, size=(Ld, H, L, d)).astype(np.int16)).cuda()
+    src_v = torch.from_numpy(rng.integers(-2 ** 15, 2 ** 15, size=(Ld, H, L, d)).astype(np.int16)).cuda()
+    idx = rng.integers(-2, C + 2, size=int(rng.integers(1, 20)))
+    valid = [int(c) for c in idx if 0 <= c < C]
+    kd, vd, pos, length = hx.run_gather(src_k.view(torch.bfloat16), src_v.view(torch.bfloat16), idx, B)
+    rk, rv, rpos = orc.gather_draft_kv(src_k.cpu().numpy(), src_v.cpu().numpy(), valid, B)
+    assert length == len(rpos) and list(pos[:length]) == list(rpos) and (pos[length:] == -1).all()
+    assert (kd.view(torch.int16)[:, :, :length].cpu().numpy() == rk).all()
+    assert (vd.view(torch.int16)[:, :, :length].cpu().numpy() == rv).all()

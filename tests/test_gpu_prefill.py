@@ -96,3 +96,18 @@ def test_full_size_prompt_sampled_rows(hx):
     # properties that hold for every row: finite, and inside the hull of V's range per column block
     assert np.isfinite(out).all()
     assert np.abs(out).max() <= np.abs(v).max() * (1 + 2.0 ** -7)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(hx, seed):
+    rng = np.random.default_rng(91000 + seed)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    g = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    n = int(rng.choice([32, 33, 63, 64, 65, 96, 127, 128, 129, 255, 300, 517, 700]))
+    tq = n if rng.random() < 0.5 else int(rng.integers(1, n + 1))
+    q, k, v = _draw(91000 + seed, tq, n, hkv * g, hkv)
+    print(f"[case] prefill random {seed}: q_len={tq} kv_len={n} Hq={hkv * g} Hkv={hkv}", flush=True)
+    ref_out, ref_lse = orc.prefill_attention(q, k, v)
+    out, lse = hx.run_prefill(q, k, v, out_dtype="f32" if seed % 3 == 0 else "bf16",
+                              kv_capacity=n + int(rng.integers(0, 3)) * 8)
+    _check(out, lse, ref_out, ref_lse, slice(None), f"prefill random {seed}")

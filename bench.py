@@ -43,6 +43,9 @@ def parse_args():
                     help="numbered workload: 4 (default) = 32 layers at a 16K prefix, the headline metric; 2 / 3 / 5 = "
                          "the single-layer shapes (2K, 8K, 32K-37 with a 128-node wide tree or a 16-node chain), run "
                          "over enough distinct K/V copies (>= 300 MB) that every launch streams cold")
+    ap.add_argument("--kv-heads", type=int, default=8,
+                    help="KV heads (8 = Llama-3.1-8B's grouped queries; 32 = multi-head attention as in the "
+                         "Vicuna-7B / LongChat-7B targets of the paper)")
     ap.add_argument("--layers", type=int, default=0, help="distinct K/V copies per step (0 = the config's own)")
     ap.add_argument("--prefix", type=int, default=0, help="prefix length (0 = the config's own)")
     ap.add_argument("--num-splits", type=int, default=0)
@@ -78,7 +81,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    Hq, Hkv, d = 32, 8, 128
+    Hq, Hkv, d = 32, args.kv_heads, 128
     L, B, topk, parent_np = {"2": (2048, 32, 32, config_tree(2)), "3": (8192, 32, 32, config_tree(3)),
                              "4": (16384, 32, 32, config_tree(4)), "5wide": (32768 - 37, 64, 16, config_tree(5, "wide")),
                              "5chain": (32768 - 37, 64, 16, config_tree(5, "chain"))}[args.config]
@@ -190,7 +193,7 @@ def main():
     achieved_gbs = bytes_per_launch / (prefix_us * 1e-6) / 1e9
     step_us = ms_per_step * 1e3
     result = {
-        "metric": "us per verification step (all layers) at 16K prefix" if (args.config == "4" and L == 16384)
+        "metric": "us per verification step (all layers) at 16K prefix" if (args.config == "4" and L == 16384 and Hkv == 8)
                   else f"us per verification step ({n_layers} layers) at prefix {L}",
         "value": round(step_us, 2),
         "unit": "us",
@@ -204,8 +207,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"config {args.config}: {n_layers} layers x (Hq=32, Hkv=8, d=128) bf16, prefix {L}, {T}-node tree, "
-                        f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x8x{cap}x128",
+            "workload": f"config {args.config}: {n_layers} layers x (Hq=32, Hkv={Hkv}, d=128) bf16, prefix {L}, {T}-node tree, "
+                        f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x{Hkv}x{cap}x128",
             "us_per_layer": round(step_us / n_layers, 2),
             "num_splits": sx.num_splits(plain.desc),
             "graph_replay": not args.no_graph,
@@ -221,7 +224,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(L) if (args.num_splits == 0 and args.config == "4") else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(L) if (args.num_splits == 0 and args.config == "4" and Hkv == 8) else None,
             "algorithmic_bytes": bytes_per_launch,
             "us_per_launch": round(prefix_us, 3),
             "mfma_TFLOPs": round(flops_per_launch / (prefix_us * 1e-6) / 1e12, 1),

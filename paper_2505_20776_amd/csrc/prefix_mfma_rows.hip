@@ -80,6 +80,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const int g = blockIdx.y;
   const int row0 = blockIdx.z * (WAVES * 32) + wave * 32;
   const int m = row0 + c32;                      // this lane's query row of the KV head
+  // a wave whose 32 rows are all padding (fewer rows than the workgroup covers) still loads its
+  // share of every tile and meets every barrier, but does no arithmetic
+  const bool wave_live = row0 < p.M;
 
   const int key_lo = split * p.keys_per_split;
   const int key_hi = min(p.L, key_lo + p.keys_per_split);
@@ -297,7 +300,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
         static_for<0, kStageTiles>([&](auto i_c) {
           constexpr int i = decltype(i_c)::value;
           const int j = s * kStageTiles + i;
-          if (j < n) tile(ic<u * kStageTiles + i>{}, j);
+          if (j < n && wave_live) tile(ic<u * kStageTiles + i>{}, j);
         });
       }
     });

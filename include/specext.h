@@ -289,6 +289,8 @@ int specext_prefill_attn(const void* q, const void* k, const void* v, void* out,
  *   specext_materialized_ld     row pitch ld of the matrix in elements (a multiple
  *                               of 64 >= prefix_len + n_tree), or a negative status
  *   workspace   device, 256-byte aligned, >= specext_materialized_bytes(desc).
+ *               Its first int32 is the status word of specext_verify_attn (1 if a parent
+ *               index was malformed; that node is then treated as a root).
  *               After specext_attn_materialized the matrix P lies at byte 256 of it:
  *               fp32 [n_q_heads][n_tree][ld]; columns 0..prefix_len-1 are the prefix
  *               keys, prefix_len..prefix_len+n_tree-1 the tree nodes (exactly 0 where

@@ -339,6 +339,7 @@ int specext_attn_materialized(const specext_desc* desc, const void* q, const voi
   p.parent = parent;
   p.out = out;
   p.lse = lse;
+  p.status = static_cast<int32_t*>(workspace);
   mp.probs = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.probs_off);
   mp.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.part_off);
   if (launch_materialized(mp, static_cast<hipStream_t>(stream)) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;

@@ -86,6 +86,12 @@ __global__ __launch_bounds__(512) void mat_logits_kernel(MatParams mp) {
 // grid (T, Hq), one thread per tree key.
 __global__ __launch_bounds__(128) void mat_tree_logits_kernel(MatParams mp) {
   const int t = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+  if (t == 0 && h == 0) {
+    // single writer of the status word: 1 if any parent index is not a topological one
+    const bool bad = j < mp.a.T && (mp.a.parent[j] >= j || mp.a.parent[j] < -1);
+    const int any_bad = __syncthreads_or(bad);
+    if (j == 0) *mp.a.status = any_bad ? 1 : 0;
+  }
   if (j >= mp.a.T) return;
   const int g = h / mp.a.G;
   bool seen = false;

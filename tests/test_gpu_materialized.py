@@ -135,3 +135,19 @@ def test_random_shapes(hx, seed):
     wl = make_workload(f"matrand{seed}", seed=seed * 17 + 3, dtype="bf16", n_q_heads=Hkv * G, n_kv_heads=Hkv,
                        head_dim=128, prefix_len=L, parent=parent, chunk_size=B, top_k=4, n_needles=0, value_std=1.0)
     _check_all(hx, wl, f"random shape {seed}")
+
+
+def test_malformed_parent_sets_status(hx):
+    rng = np.random.default_rng(6)
+    wl = make_workload("badparent", seed=6, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, prefix_len=100,
+                       parent=eagle_style_tree(20, 5, rng), chunk_size=32, top_k=4, n_needles=0, value_std=1.0)
+    res = hx.run_materialized(wl)
+    assert int(res["workspace"][:4].view(torch.int32).item()) == 0
+    wl.parent = wl.parent.copy()
+    wl.parent[7] = 9                                             # not a topological parent: node 7 becomes a root
+    res = hx.run_materialized(wl)
+    assert int(res["workspace"][:4].view(torch.int32).item()) == 1
+    fixed = wl.parent.copy()
+    fixed[7] = -1
+    ref_p = orc.attention_probabilities(wl.q, wl.k_prefix, wl.k_tree, fixed)
+    assert np.abs(res["probs"] - ref_p).max() <= PROB_EPS * ref_p.max()

@@ -248,17 +248,35 @@ __device__ __forceinline__ int chunk_tokens(int c, int n_chunks, int src_len, in
 }
 
 // grid (max_idx, n_layers * n_heads, 2): one workgroup copies one chunk of one
-// (layer, head) of K (z = 0) or V (z = 1), 16 bytes per thread per step.
+// (layer, head) of K (z = 0) or V (z = 1), 16 bytes per thread per step.  The workgroups
+// of (layer, head) 0 of K also do the bookkeeping: each writes the original positions of
+// its chunk's tokens, and the one of list entry 0 the total and the -1 behind it.
 __global__ __launch_bounds__(256) void gather_copy_kernel(const uint4* __restrict__ k_src, const uint4* __restrict__ v_src,
                                                          uint4* __restrict__ k_dst, uint4* __restrict__ v_dst,
                                                          const int* __restrict__ idx, const int* __restrict__ n_idx,
                                                          int max_idx, int src_len, int src_cap, int dst_cap,
-                                                         int row_vecs, int chunk_size) {
+                                                         int row_vecs, int chunk_size, int* __restrict__ pos_out,
+                                                         int* __restrict__ len_out) {
   __shared__ int sh_off[4];
   const int r = blockIdx.x;
   const int n_used = n_idx ? min(max(*n_idx, 0), max_idx) : max_idx;
-  if (r >= n_used) return;
   const int n_chunks = (src_len + chunk_size - 1) / chunk_size;
+  const bool book = blockIdx.y == 0 && blockIdx.z == 0 && (pos_out || len_out);
+  if (book && r == 0) {
+    // tokens of the whole list (fixed order), then the tail of pos_out
+    int part = 0;
+    for (int i = threadIdx.x; i < n_used; i += blockDim.x) part += chunk_tokens(idx[i], n_chunks, src_len, chunk_size);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+    if ((threadIdx.x & 63) == 0) sh_off[threadIdx.x >> 6] = part;
+    __syncthreads();
+    const int total = sh_off[0] + sh_off[1] + sh_off[2] + sh_off[3];
+    __syncthreads();
+    if (pos_out)
+      for (int i = total + threadIdx.x; i < dst_cap; i += blockDim.x) pos_out[i] = -1;
+    if (len_out && threadIdx.x == 0) *len_out = total;
+  }
+  if (r >= n_used) return;
   const int c = idx[r];
   const int tokens = chunk_tokens(c, n_chunks, src_len, chunk_size);
   if (tokens == 0) return;
@@ -270,6 +288,8 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(const uint4* __restric
   if ((threadIdx.x & 63) == 0) sh_off[threadIdx.x >> 6] = part;
   __syncthreads();
   const int dst_tok = sh_off[0] + sh_off[1] + sh_off[2] + sh_off[3];
+  if (book && pos_out)
+    for (int tk = threadIdx.x; tk < tokens; tk += blockDim.x) pos_out[dst_tok + tk] = c * chunk_size + tk;
 
   const int64_t lh = blockIdx.y;
   const uint4* src = (blockIdx.z == 0 ? k_src : v_src) + (lh * src_cap + static_cast<int64_t>(c) * chunk_size) * row_vecs;
@@ -278,9 +298,10 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(const uint4* __restric
   for (int i = threadIdx.x; i < n_vecs; i += blockDim.x) dst[i] = src[i];
 }
 
-// One workgroup: original positions of the kept tokens, -1 behind them, and the total.
-// Entry r of the list is handled by thread r (lists longer than the block go round
-// by round, carrying the running offset), offsets come from a block scan.
+// The bookkeeping alone (an empty list or no (layer, head) to copy): original positions of
+// the kept tokens, -1 behind them, and the total.  One workgroup; entry r of the list is
+// handled by thread r (lists longer than the block go round by round, carrying the
+// running offset), offsets come from a block scan.
 __global__ __launch_bounds__(256) void gather_meta_kernel(const int* __restrict__ idx, const int* __restrict__ n_idx,
                                                          int max_idx, int src_len, int dst_cap, int chunk_size,
                                                          int* __restrict__ pos_out, int* __restrict__ len_out) {
@@ -332,17 +353,17 @@ hipError_t launch_gather(const void* k_src, const void* v_src, void* k_dst, void
                          const int32_t* idx, const int32_t* n_idx, int32_t max_idx, int32_t n_lh,
                          int32_t src_len, int32_t src_cap, int32_t dst_cap, int32_t row_bytes,
                          int32_t chunk_size, int32_t* pos_out, int32_t* len_out, hipStream_t stream) {
-  if (pos_out || len_out) {
-    gather_meta_kernel<<<dim3(1), dim3(256), 0, stream>>>(idx, n_idx, max_idx, src_len, dst_cap, chunk_size,
-                                                          pos_out, len_out);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   if (max_idx > 0 && n_lh > 0) {
     dim3 grid(max_idx, n_lh, 2);
     gather_copy_kernel<<<grid, dim3(256), 0, stream>>>(
         static_cast<const uint4*>(k_src), static_cast<const uint4*>(v_src), static_cast<uint4*>(k_dst),
-        static_cast<uint4*>(v_dst), idx, n_idx, max_idx, src_len, src_cap, dst_cap, row_bytes / 16, chunk_size);
+        static_cast<uint4*>(v_dst), idx, n_idx, max_idx, src_len, src_cap, dst_cap, row_bytes / 16, chunk_size,
+        pos_out, len_out);
+    return hipGetLastError();
+  }
+  if (pos_out || len_out) {
+    gather_meta_kernel<<<dim3(1), dim3(256), 0, stream>>>(idx, n_idx, max_idx, src_len, dst_cap, chunk_size,
+                                                          pos_out, len_out);
     return hipGetLastError();
   }
   return hipSuccess;

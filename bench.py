@@ -174,6 +174,15 @@ def main():
         t1 = time.perf_counter()
         ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+        # ---- the same K steps once more, each between its own pair of events: median and minimum ----
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for a, b in evs:
+            a.record(stream)
+            run_step()
+            b.record(stream)
+        stream.synchronize()
+        per_step = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+
         # ---- dominant kernel: prefix pass, HIP events on the launch stream ----
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
@@ -210,6 +219,8 @@ def main():
             "workload": f"config {args.config}: {n_layers} layers x (Hq=32, Hkv={Hkv}, d=128) bf16, prefix {L}, {T}-node tree, "
                         f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x{Hkv}x{cap}x128",
             "us_per_layer": round(step_us / n_layers, 2),
+            "step_us_median": round(per_step[len(per_step) // 2], 2),
+            "step_us_min": round(per_step[0], 2),
             "num_splits": sx.num_splits(plain.desc),
             "graph_replay": not args.no_graph,
             "last_layer": args.last_layer,

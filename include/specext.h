@@ -66,6 +66,7 @@ typedef enum specext_dtype {
 
 #define SPECEXT_MAX_TREE 128           /* largest supported n_tree */
 #define SPECEXT_MAX_SPLITS 256         /* largest supported num_splits */
+#define SPECEXT_STATIC_SCRATCH_MIB 48  /* scratch of specext_verify_attn_static, MiB per GPU */
 
 /*
  * Problem descriptor (plain data).  Set struct_size = sizeof(specext_desc).
@@ -129,6 +130,32 @@ int specext_verify_attn(const specext_desc* desc, const void* q, const void* k_p
                         const void* v_prefix, const void* k_tree, const void* v_tree,
                         const int32_t* parent, void* out, float* lse, void* workspace,
                         size_t workspace_bytes, void* stream);
+
+/*
+ * specext_verify_attn for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same inputs, outputs, kernels and results as specext_verify_attn; the
+ * split partials live in a scratch array of SPECEXT_STATIC_SCRATCH_MIB MiB that is
+ * part of the library's device code (every GPU that loads the library holds its own
+ * copy until the process ends).  The call allocates and frees nothing.
+ *
+ *   status_out  device int32 [1] that receives the status word (0, or 1 for a
+ *               malformed parent index); may be NULL
+ *
+ * Limits: a descriptor whose specext_workspace_bytes exceeds the scratch array is
+ * rejected with SPECEXT_ERR_WORKSPACE_TOO_SMALL before anything is launched (the
+ * Llama-3.1-8B layer shape fits at every prefix length with a 60-node tree at up to
+ * 48 splits and with a 128-node tree at up to 22, the automatic split counts
+ * included); want_scores != 0 is SPECEXT_ERR_UNSUPPORTED, because the
+ * chunk partial sums must outlive the call for specext_chunk_scores - the one layer
+ * that feeds the retrieval uses specext_verify_attn.  Every call on a GPU shares that
+ * GPU's array: calls that overlap in time on one GPU (different streams) race on it
+ * and must not be made; calls on one stream, or otherwise ordered, are safe.
+ */
+int specext_verify_attn_static(const specext_desc* desc, const void* q, const void* k_prefix,
+                               const void* v_prefix, const void* k_tree, const void* v_tree,
+                               const int32_t* parent, void* out, float* lse, int32_t* status_out,
+                               void* stream);
 
 /*
  * Chunk scores (Sec. 3.2.1): scores[r][c] = mean over query heads of the mean,

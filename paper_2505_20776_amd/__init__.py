@@ -6,8 +6,8 @@ Python binding over it.  PyTorch supplies device memory and streams only.
 """
 from .binding import (prefill_attn, attn_materialized, chunk_scores_materialized, materialized_bytes, materialized_ld, accept_greedy, chunk_scores_accepted, commit_tree_kv, SPECEXT_BF16, SPECEXT_F32, SPECEXT_FLAG_PREFIX_ONLY, SPECEXT_FLAG_VALU_PREFIX, SPECEXT_MAX_SPLITS, SPECEXT_MAX_TREE, SpecextError,
                       chunk_scores, gather_draft_kv, load_library, make_desc, num_splits, select_chunks,
-                      specext_desc, strerror, verify_attn, workspace_bytes)
+                      specext_desc, strerror, verify_attn, verify_attn_static, workspace_bytes)
 
 __all__ = ["prefill_attn", "attn_materialized", "chunk_scores_materialized", "materialized_bytes", "materialized_ld", "accept_greedy", "chunk_scores_accepted", "commit_tree_kv", "SPECEXT_BF16", "SPECEXT_F32", "SPECEXT_FLAG_PREFIX_ONLY", "SPECEXT_FLAG_VALU_PREFIX", "SPECEXT_MAX_SPLITS", "SPECEXT_MAX_TREE", "SpecextError",
            "chunk_scores", "gather_draft_kv", "load_library", "make_desc", "num_splits", "select_chunks",
-           "specext_desc", "strerror", "verify_attn", "workspace_bytes"]
+           "specext_desc", "strerror", "verify_attn", "verify_attn_static", "workspace_bytes"]

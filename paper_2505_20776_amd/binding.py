@@ -30,7 +30,7 @@ EXPORTED = ("specext_strerror", "specext_workspace_bytes", "specext_num_splits",
             "specext_chunk_scores", "specext_select_chunks", "specext_gather_draft_kv", "specext_accept_greedy",
             "specext_commit_tree_kv", "specext_chunk_scores_accepted", "specext_materialized_bytes",
             "specext_materialized_ld", "specext_attn_materialized", "specext_chunk_scores_materialized",
-            "specext_prefill_attn")
+            "specext_prefill_attn", "specext_verify_attn_static")
 
 
 class SpecextError(RuntimeError):
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.specext_num_splits.argtypes = [dp]
     lib.specext_verify_attn.restype = ctypes.c_int
     lib.specext_verify_attn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.specext_verify_attn_static.restype = ctypes.c_int
+    lib.specext_verify_attn_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.specext_chunk_scores.restype = ctypes.c_int
     lib.specext_chunk_scores.argtypes = [dp, vp, sz, i32, vp, vp]
     lib.specext_select_chunks.restype = ctypes.c_int
@@ -166,6 +168,16 @@ def verify_attn(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, w
                                             _ptr(workspace), workspace_nbytes, _stream(stream))
     if check:
         _check(rc, "specext_verify_attn")
+    return rc
+
+
+def verify_attn_static(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, status_out=None,
+                       stream=None, check: bool = True) -> int:
+    rc = load_library().specext_verify_attn_static(ctypes.byref(desc), _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
+                                                   _ptr(k_tree), _ptr(v_tree), _ptr(parent), _ptr(out), _ptr(lse),
+                                                   _ptr(status_out), _stream(stream))
+    if check:
+        _check(rc, "specext_verify_attn_static")
     return rc
 
 

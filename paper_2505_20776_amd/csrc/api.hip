@@ -202,6 +202,62 @@ int resolve_materialized(const specext_desc* d, MatParams* mp, MatLayout* w) {
   return SPECEXT_OK;
 }
 
+// Scratch memory of specext_verify_attn_static: one array per GPU that loads this code
+// object, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address it returns (one per device) is what the kernels
+// are given.
+constexpr size_t kStaticScratchBytes = size_t{SPECEXT_STATIC_SCRATCH_MIB} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+void* static_scratch_of_current_device() {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* ptr = cached[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+  cached[dev].store(ptr, std::memory_order_release);
+  return ptr;
+}
+
+// specext_verify_attn on an explicit workspace; status_word != nullptr redirects the status word
+int verify_attn_on(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
+                   const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
+                   void* workspace, size_t workspace_bytes, int32_t* status_word, void* stream) {
+  AttnParams p;
+  const int rc = resolve(desc, &p);
+  if (rc != SPECEXT_OK) return rc;
+  if (!q || !k_tree || !v_tree || !parent || !out || !workspace) return SPECEXT_ERR_INVALID_ARG;
+  if (p.L > 0 && (!k_prefix || !v_prefix)) return SPECEXT_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(k_tree) || !aligned16(v_tree) ||
+      !aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
+      (reinterpret_cast<uintptr_t>(parent) & 3u) != 0 || (reinterpret_cast<uintptr_t>(lse) & 3u) != 0)
+    return SPECEXT_ERR_UNSUPPORTED;
+  const WorkspaceLayout w = layout_of(p);
+  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  p.q = q;
+  p.kp = k_prefix;
+  p.vp = v_prefix;
+  p.kt = k_tree;
+  p.vt = v_tree;
+  p.parent = parent;
+  p.out = out;
+  p.lse = lse;
+  bind_workspace(&p, w, workspace);
+  if (status_word) p.status = status_word;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p.S > 0) {
+    const hipError_t e = p.use_mfma == 2   ? launch_prefix_mfma_rows(p, s)
+                         : p.use_mfma == 1 ? launch_prefix_mfma(p, s)
+                                           : launch_prefix_generic(p, s);
+    if (e != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  }
+  if (desc->flags & SPECEXT_FLAG_PREFIX_ONLY) return SPECEXT_OK;
+  if (launch_tree_merge(p, s) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
 }  // namespace
 }  // namespace specext
 
@@ -236,36 +292,25 @@ int specext_num_splits(const specext_desc* desc) {
 int specext_verify_attn(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
                         const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
                         void* workspace, size_t workspace_bytes, void* stream) {
+  return verify_attn_on(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, workspace, workspace_bytes,
+                        nullptr, stream);
+}
+
+int specext_verify_attn_static(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
+                               const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
+                               int32_t* status_out, void* stream) {
   AttnParams p;
   const int rc = resolve(desc, &p);
   if (rc != SPECEXT_OK) return rc;
-  if (!q || !k_tree || !v_tree || !parent || !out || !workspace) return SPECEXT_ERR_INVALID_ARG;
-  if (p.L > 0 && (!k_prefix || !v_prefix)) return SPECEXT_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(k_tree) || !aligned16(v_tree) ||
-      !aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
-      (reinterpret_cast<uintptr_t>(parent) & 3u) != 0 || (reinterpret_cast<uintptr_t>(lse) & 3u) != 0)
-    return SPECEXT_ERR_UNSUPPORTED;
-  const WorkspaceLayout w = layout_of(p);
-  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
-  p.q = q;
-  p.kp = k_prefix;
-  p.vp = v_prefix;
-  p.kt = k_tree;
-  p.vt = v_tree;
-  p.parent = parent;
-  p.out = out;
-  p.lse = lse;
-  bind_workspace(&p, w, workspace);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (p.S > 0) {
-    const hipError_t e = p.use_mfma == 2   ? launch_prefix_mfma_rows(p, s)
-                         : p.use_mfma == 1 ? launch_prefix_mfma(p, s)
-                                           : launch_prefix_generic(p, s);
-    if (e != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
-  }
-  if (desc->flags & SPECEXT_FLAG_PREFIX_ONLY) return SPECEXT_OK;
-  if (launch_tree_merge(p, s) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
-  return SPECEXT_OK;
+  // the chunk partial sums would have to outlive the call for specext_chunk_scores, which
+  // takes the caller's workspace: the layer that feeds the retrieval uses specext_verify_attn
+  if (p.want_scores) return SPECEXT_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(status_out) & 3u) return SPECEXT_ERR_UNSUPPORTED;
+  if (layout_of(p).total > kStaticScratchBytes) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  void* ws = static_scratch_of_current_device();
+  if (!ws) return SPECEXT_ERR_LAUNCH_FAILED;
+  return verify_attn_on(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, ws, kStaticScratchBytes,
+                        status_out, stream);
 }
 
 int specext_chunk_scores(const specext_desc* desc, const void* workspace, size_t workspace_bytes,

@@ -63,9 +63,24 @@ typedef enum specext_dtype {
  * before the tree pass and merge, so out / lse are not written.  For timing the
  * prefix kernel on its own. */
 #define SPECEXT_FLAG_PREFIX_ONLY 2u
+/* desc->flags: run the tree pass and the merge as the tail of the prefix launch instead
+ * of as a second launch, where that is possible (bf16, head_dim 128, more than 32 rows per
+ * KV head, all workgroups resident at once; otherwise the flag has no effect).  The
+ * workgroups hand their split results to each other through the workspace header, which
+ * must have been prepared with specext_workspace_init.  Same results as the two-launch
+ * form up to the rounding of a different (fixed) summation order; bit-reproducible from
+ * run to run.  On MI355X the two launches measure faster at every prefix length (a
+ * dependent trip through memory costs more than the launch boundary it replaces), so this
+ * form is off unless asked for. */
+#define SPECEXT_FLAG_FUSED_MERGE 4u
+/* desc->flags, with SPECEXT_FLAG_FUSED_MERGE: a workgroup polls for the other splits'
+ * results once instead of up to 65537 times before it leaves its rows to the workgroup
+ * that finishes last.  Results are unchanged; for testing that hand-over. */
+#define SPECEXT_FLAG_SHORT_WAIT 8u
 
 #define SPECEXT_MAX_TREE 128           /* largest supported n_tree */
 #define SPECEXT_MAX_SPLITS 256         /* largest supported num_splits */
+#define SPECEXT_WORKSPACE_HEADER_BYTES 82176   /* head of every workspace, see specext_workspace_init */
 #define SPECEXT_STATIC_SCRATCH_MIB 48  /* scratch of specext_verify_attn_static, MiB per GPU */
 
 /*
@@ -108,6 +123,20 @@ const char* specext_strerror(int status);
 size_t specext_workspace_bytes(const specext_desc* desc);
 
 /*
+ * Prepare a workspace for specext_verify_attn with SPECEXT_FLAG_FUSED_MERGE: once after
+ * it is allocated (or whenever its first SPECEXT_WORKSPACE_HEADER_BYTES were overwritten
+ * by something else), before its first use, on a stream ordered before that use.  The
+ * head of every workspace does not depend on the descriptor - status word, an
+ * initialisation mark and the hand-over blocks through which the workgroups of one
+ * launch pass their split results to each other; every call leaves them ready for the
+ * next, so one workspace serves any sequence of calls and descriptors after a single
+ * init.  workspace_bytes must be at least SPECEXT_WORKSPACE_HEADER_BYTES and the pointer
+ * 256-byte aligned.  A fused call on a workspace that was never initialised sets the
+ * status word to 2 and writes neither out nor lse.  Calls without the flag need no init.
+ */
+int specext_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Hybrid Tree Attention for one layer (Sec. 3.1).
  *
  *   q         [T, Hq, d]   queries of the tree tokens           (desc->dtype)
@@ -122,7 +151,9 @@ size_t specext_workspace_bytes(const specext_desc* desc);
  *
  * Pointers must be 16-byte aligned and strides multiples of 8 elements.
  * The first int32 of the workspace is a status word: 0 after a good call,
- * 1 if some parent[i] was >= i or < -1 (that node is then treated as a root).
+ * 1 if some parent[i] was >= i or < -1 (that node is then treated as a root),
+ * 2 if SPECEXT_FLAG_FUSED_MERGE was set and the workspace was never initialised
+ * (nothing was computed).
  * With want_scores the workspace afterwards holds what specext_chunk_scores
  * consumes; it stays valid until the next call that uses this workspace.
  */
@@ -345,6 +376,27 @@ int specext_chunk_scores_materialized(const specext_desc* desc, const void* work
  * valid).  Returns a negative specext_status on an invalid descriptor.
  */
 int specext_num_splits(const specext_desc* desc);
+
+/*
+ * Measurement aids, not part of the method: what the GPU at hand sustains in a pure
+ * HBM read stream and in pure dense bf16 matrix-core work, so that a benchmark can
+ * quote the kernels above against measured ceilings next to the published ones
+ * (the roofline that bounds the prefix pass of Sec. 3.1: K/V bytes per launch against
+ * HBM bandwidth, 4 d T G Hkv L flops per launch against the bf16 matrix rate).
+ *
+ * specext_calib_stream_read: reads every byte of [src, src + bytes) once with
+ *   coalesced 16-byte loads.  src device, 16-byte aligned; bytes a positive multiple of
+ *   32768; sink: device uint32 [1] or NULL (never written for real data).  Time it with
+ *   events on `stream`; bytes / time is the read bandwidth.  Use a buffer much larger
+ *   than the 256 MB last-level cache.
+ * specext_calib_mfma: `workgroups` workgroups of four wavefronts, each wavefront
+ *   issuing iters x 16 matrix instructions (tile = 32: v_mfma_f32_32x32x16_bf16,
+ *   tile = 16: v_mfma_f32_16x16x32_bf16) on register operands of roughly unit variance
+ *   and nothing else.  Returns the number of floating-point operations of the launch
+ *   (> 0), or a negative specext_status.  sink: device float [1] or NULL.
+ */
+int specext_calib_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+int64_t specext_calib_mfma(int32_t iters, int32_t tile, int32_t workgroups, float* sink, void* stream);
 
 #ifdef __cplusplus
 }

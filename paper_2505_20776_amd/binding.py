@@ -22,6 +22,9 @@ SPECEXT_MAX_TREE = 128
 SPECEXT_MAX_SPLITS = 256
 SPECEXT_FLAG_VALU_PREFIX = 1
 SPECEXT_FLAG_PREFIX_ONLY = 2
+SPECEXT_FLAG_FUSED_MERGE = 4
+SPECEXT_FLAG_SHORT_WAIT = 8
+WORKSPACE_HEADER_BYTES = 82176
 
 STATUS_NAMES = {0: "SPECEXT_OK", -1: "SPECEXT_ERR_INVALID_ARG", -2: "SPECEXT_ERR_UNSUPPORTED",
                 -3: "SPECEXT_ERR_WORKSPACE_TOO_SMALL", -4: "SPECEXT_ERR_LAUNCH_FAILED"}
@@ -30,7 +33,8 @@ EXPORTED = ("specext_strerror", "specext_workspace_bytes", "specext_num_splits",
             "specext_chunk_scores", "specext_select_chunks", "specext_gather_draft_kv", "specext_accept_greedy",
             "specext_commit_tree_kv", "specext_chunk_scores_accepted", "specext_materialized_bytes",
             "specext_materialized_ld", "specext_attn_materialized", "specext_chunk_scores_materialized",
-            "specext_prefill_attn", "specext_verify_attn_static")
+            "specext_prefill_attn", "specext_verify_attn_static", "specext_workspace_init",
+            "specext_calib_stream_read", "specext_calib_mfma")
 
 
 class SpecextError(RuntimeError):
@@ -75,6 +79,8 @@ def load_library() -> ctypes.CDLL:
     lib.specext_num_splits.argtypes = [dp]
     lib.specext_verify_attn.restype = ctypes.c_int
     lib.specext_verify_attn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.specext_workspace_init.restype = ctypes.c_int
+    lib.specext_workspace_init.argtypes = [vp, sz, vp]
     lib.specext_verify_attn_static.restype = ctypes.c_int
     lib.specext_verify_attn_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.specext_chunk_scores.restype = ctypes.c_int
@@ -102,6 +108,10 @@ def load_library() -> ctypes.CDLL:
     lib.specext_prefill_attn.restype = ctypes.c_int
     lib.specext_prefill_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, ctypes.c_float,
                                          i64, i64, i64, i64, i64, i64, vp]
+    lib.specext_calib_stream_read.restype = ctypes.c_int
+    lib.specext_calib_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.specext_calib_mfma.restype = ctypes.c_int64
+    lib.specext_calib_mfma.argtypes = [i32, i32, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -157,6 +167,15 @@ def workspace_bytes(desc: specext_desc) -> int:
 
 def num_splits(desc: specext_desc) -> int:
     return int(load_library().specext_num_splits(ctypes.byref(desc)))
+
+
+def workspace_init(workspace, workspace_nbytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_nbytes is None:
+        workspace_nbytes = workspace.numel() * workspace.element_size()
+    rc = load_library().specext_workspace_init(_ptr(workspace), workspace_nbytes, _stream(stream))
+    if check:
+        _check(rc, "specext_workspace_init")
+    return rc
 
 
 def verify_attn(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, workspace,
@@ -292,4 +311,21 @@ def prefill_attn(q, k, v, out, lse, n_q_heads: int, n_kv_heads: int, head_dim: i
                                              _stream(stream))
     if check:
         _check(rc, "specext_prefill_attn")
+    return rc
+
+
+def calib_stream_read(src, nbytes: int, sink=None, stream=None, check: bool = True) -> int:
+    rc = load_library().specext_calib_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream))
+    if check:
+        _check(rc, "specext_calib_stream_read")
+    return rc
+
+
+def calib_mfma(iters: int, tile: int = 32, workgroups: int = 512, sink=None, stream=None,
+                    check: bool = True) -> int:
+    """Returns the floating-point operations of the launch."""
+    rc = int(load_library().specext_calib_mfma(int(iters), int(tile), int(workgroups), _ptr(sink),
+                                                    _stream(stream)))
+    if check and rc < 0:
+        _check(rc, "specext_calib_mfma")
     return rc

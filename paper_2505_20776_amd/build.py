@@ -18,7 +18,7 @@ EXTRA_FLAGS = {"prefix_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                "prefix_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"],
                "prefill_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"]}
 SOURCES = ["api.hip", "prefix_generic.hip", "prefix_mfma.hip", "prefix_mfma_rows.hip", "tree_merge.hip", "retrieval.hip",
-           "accept.hip", "materialized.hip", "prefill_rows.hip"]
+           "accept.hip", "materialized.hip", "prefill_rows.hip", "calibrate.hip"]
 
 
 def hipcc_path() -> str:

@@ -15,6 +15,23 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct WorkspaceLayout {
   size_t status_off, lse2_off, part_ml_off, part_o_off, chunk_off, total;
 };
+// Head of every workspace, the same for every descriptor (so that one specext_workspace_init
+// serves whatever problems the workspace is later used for): status word at byte 0, the
+// initialisation mark at byte 8, the hand-over blocks of the fused merge tail from byte 256 on.
+constexpr size_t kCookieOff = 8;
+constexpr size_t kSyncOff = 256;
+constexpr size_t kHeaderBytes = kSyncOff + kMaxSyncBlocks * sizeof(SyncBlock);
+static_assert(kHeaderBytes == SPECEXT_WORKSPACE_HEADER_BYTES, "the header states the size of the workspace head");
+constexpr int kDefaultSpinLimit = 1 << 16;     // polls of roughly a microsecond each
+
+__global__ void workspace_init_kernel(uint32_t* head) {
+  for (unsigned i = threadIdx.x; i < kHeaderBytes / 4; i += blockDim.x) {
+    uint32_t v = 0;
+    if (i == kCookieOff / 4) v = static_cast<uint32_t>(kWorkspaceCookie);
+    if (i == kCookieOff / 4 + 1) v = static_cast<uint32_t>(kWorkspaceCookie >> 32);
+    head[i] = v;
+  }
+}
 
 // Compute-unit count of the current device, cached per process.
 int device_cu_count() {
@@ -46,7 +63,8 @@ int resolve(const specext_desc* d, AttnParams* p) {
   if (d->n_q_heads % d->n_kv_heads != 0) return SPECEXT_ERR_INVALID_ARG;
   if (d->want_scores && d->chunk_size <= 0) return SPECEXT_ERR_INVALID_ARG;
   if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return SPECEXT_ERR_INVALID_ARG;
-  if (d->reserved != 0 || (d->flags & ~(SPECEXT_FLAG_VALU_PREFIX | SPECEXT_FLAG_PREFIX_ONLY)) != 0) return SPECEXT_ERR_INVALID_ARG;
+  if (d->reserved != 0 || (d->flags & ~(SPECEXT_FLAG_VALU_PREFIX | SPECEXT_FLAG_PREFIX_ONLY | SPECEXT_FLAG_FUSED_MERGE |
+                                       SPECEXT_FLAG_SHORT_WAIT)) != 0) return SPECEXT_ERR_INVALID_ARG;
   if (d->dtype != SPECEXT_F32 && d->dtype != SPECEXT_BF16) return SPECEXT_ERR_UNSUPPORTED;
   if (d->out_dtype != SPECEXT_F32 && d->out_dtype != d->dtype) return SPECEXT_ERR_UNSUPPORTED;
   if (d->head_dim != 64 && d->head_dim != 128) return SPECEXT_ERR_UNSUPPORTED;
@@ -132,6 +150,14 @@ int resolve(const specext_desc* d, AttnParams* p) {
   per = (per + unit - 1) / unit * unit;
   p->keys_per_split = static_cast<int32_t>(per);
   p->S = static_cast<int32_t>((p->L + per - 1) / per);
+  // Tree pass and merge as the tail of the prefix launch (on request): row-split kernel
+  // only, and only when all its workgroups fit the device at once (one per compute unit),
+  // so that in the normal case nobody waits for a workgroup that has not started.
+  const int64_t row_groups = (p->M + p->rows_per_group - 1) / p->rows_per_group;
+  p->spin_limit = (d->flags & SPECEXT_FLAG_SHORT_WAIT) ? 0 : kDefaultSpinLimit;
+  p->fused_tail = p->use_mfma == 2 && p->S <= 64 && p->L > 0 && p->Hkv * row_groups <= kMaxSyncBlocks &&
+                  p->S * p->Hkv * row_groups <= device_cu_count() &&
+                  (d->flags & SPECEXT_FLAG_FUSED_MERGE) && !(d->flags & SPECEXT_FLAG_PREFIX_ONLY);
   return SPECEXT_OK;
 }
 
@@ -140,7 +166,7 @@ WorkspaceLayout layout_of(const AttnParams& p) {
   const size_t rows = static_cast<size_t>(p.Hq) * p.T;
   size_t off = 0;
   w.status_off = off;
-  off += kAlign;
+  off += kHeaderBytes;
   w.lse2_off = off;
   off += align_up(rows * sizeof(float));
   w.part_ml_off = off;
@@ -160,6 +186,8 @@ void bind_workspace(AttnParams* p, const WorkspaceLayout& w, void* workspace) {
   p->part_ml = reinterpret_cast<float*>(base + w.part_ml_off);
   p->part_o = reinterpret_cast<float*>(base + w.part_o_off);
   p->chunk_part = p->want_scores ? reinterpret_cast<float*>(base + w.chunk_off) : nullptr;
+  p->sync = reinterpret_cast<SyncBlock*>(base + kSyncOff);
+  p->cookie = reinterpret_cast<const uint64_t*>(base + kCookieOff);
 }
 
 inline bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
@@ -224,7 +252,7 @@ void* static_scratch_of_current_device() {
 // specext_verify_attn on an explicit workspace; status_word != nullptr redirects the status word
 int verify_attn_on(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
                    const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
-                   void* workspace, size_t workspace_bytes, int32_t* status_word, void* stream) {
+                   void* workspace, size_t workspace_bytes, int32_t* status_word, bool library_memory, void* stream) {
   AttnParams p;
   const int rc = resolve(desc, &p);
   if (rc != SPECEXT_OK) return rc;
@@ -245,6 +273,7 @@ int verify_attn_on(const specext_desc* desc, const void* q, const void* k_prefix
   p.out = out;
   p.lse = lse;
   bind_workspace(&p, w, workspace);
+  if (library_memory) p.cookie = nullptr;      // the static scratch array: zero when the code object is loaded, cleared by every call
   if (status_word) p.status = status_word;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (p.S > 0) {
@@ -253,7 +282,7 @@ int verify_attn_on(const specext_desc* desc, const void* q, const void* k_prefix
                                            : launch_prefix_generic(p, s);
     if (e != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
   }
-  if (desc->flags & SPECEXT_FLAG_PREFIX_ONLY) return SPECEXT_OK;
+  if ((desc->flags & SPECEXT_FLAG_PREFIX_ONLY) || (p.fused_tail && p.S > 0)) return SPECEXT_OK;
   if (launch_tree_merge(p, s) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
   return SPECEXT_OK;
 }
@@ -282,6 +311,14 @@ size_t specext_workspace_bytes(const specext_desc* desc) {
   return layout_of(p).total;
 }
 
+int specext_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace) return SPECEXT_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) return SPECEXT_ERR_UNSUPPORTED;
+  if (workspace_bytes < kHeaderBytes) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  workspace_init_kernel<<<1, 1024, 0, static_cast<hipStream_t>(stream)>>>(static_cast<uint32_t*>(workspace));
+  return hipGetLastError() == hipSuccess ? SPECEXT_OK : SPECEXT_ERR_LAUNCH_FAILED;
+}
+
 int specext_num_splits(const specext_desc* desc) {
   AttnParams p;
   const int rc = resolve(desc, &p);
@@ -293,7 +330,7 @@ int specext_verify_attn(const specext_desc* desc, const void* q, const void* k_p
                         const void* k_tree, const void* v_tree, const int32_t* parent, void* out, float* lse,
                         void* workspace, size_t workspace_bytes, void* stream) {
   return verify_attn_on(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, workspace, workspace_bytes,
-                        nullptr, stream);
+                        nullptr, false, stream);
 }
 
 int specext_verify_attn_static(const specext_desc* desc, const void* q, const void* k_prefix, const void* v_prefix,
@@ -310,7 +347,7 @@ int specext_verify_attn_static(const specext_desc* desc, const void* q, const vo
   void* ws = static_scratch_of_current_device();
   if (!ws) return SPECEXT_ERR_LAUNCH_FAILED;
   return verify_attn_on(desc, q, k_prefix, v_prefix, k_tree, v_tree, parent, out, lse, ws, kStaticScratchBytes,
-                        status_out, stream);
+                        status_out, true, stream);
 }
 
 int specext_chunk_scores(const specext_desc* desc, const void* workspace, size_t workspace_bytes,

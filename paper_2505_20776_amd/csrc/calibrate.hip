@@ -1,0 +1,119 @@
+// Measurement aids (not part of the method): what this GPU sustains in a pure HBM read
+// stream and in pure dense bf16 matrix-core work, so that a benchmark can quote the
+// verification kernels against measured ceilings next to the published ones.
+#include "mfma_util.h"
+
+namespace specext {
+namespace {
+
+constexpr int kStreamThreads = 256;
+constexpr int kStreamUnroll = 8;                // 16-byte loads in flight per thread
+
+// Every byte of [src, src + n_vec * 16) is read exactly once with coalesced 16-byte loads;
+// the XOR of everything decides a store that never happens for real data, so that the
+// loads cannot be dropped.
+__global__ __launch_bounds__(kStreamThreads) void calib_stream_kernel(const uintx4* __restrict__ src, size_t n_vec,
+                                                                      uint32_t* sink) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * kStreamThreads * kStreamUnroll;
+  uintx4 acc = {0u, 0u, 0u, 0u};
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kStreamThreads * kStreamUnroll + threadIdx.x; i < n_vec; i += stride) {
+    uintx4 v[kStreamUnroll];
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) v[u] = __builtin_nontemporal_load(src + i + u * kStreamThreads);
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) acc ^= v[u];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && sink) sink[0] = 1u;
+}
+
+// bf16 operands that look like attention data (roughly unit-variance values, all lanes
+// different): the power a matrix instruction draws depends on how many bits toggle
+__device__ __forceinline__ bf16x8 operand_of(uint32_t seed) {
+  bf16x8 out;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    seed = seed * 1664525u + 1013904223u;
+    const float f = (static_cast<float>(seed >> 8) * (1.0f / 8388608.0f) - 1.0f) * 1.7f;     // uniform in [-1.7, 1.7)
+    out[e] = __builtin_bit_cast(__bf16, float_to_bf16_bits(f));
+  }
+  return out;
+}
+
+// Nothing but matrix instructions: every wave keeps four independent accumulator tiles
+// and issues 16 products per loop iteration from operands held in registers.
+// TILE32: v_mfma_f32_32x32x16_bf16 (32768 flop each), else v_mfma_f32_16x16x32_bf16 (16384 flop).
+template <bool TILE32>
+__global__ __launch_bounds__(256) void calib_mfma_kernel(int iters, float* sink) {
+  const uint32_t seed = (blockIdx.x * 256u + threadIdx.x) * 2654435761u;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = operand_of(seed + 17u * i);
+    b[i] = operand_of(seed + 101u * i + 7u);
+  }
+  float total = 0.f;
+  if constexpr (TILE32) {
+    floatx16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + rep) & 3], b[i], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) total += acc[i][r];
+  } else {
+    floatx4 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[(i + rep) & 3], b[i], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) total += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  }
+  if (total == 12345.678f && sink) sink[0] = total;
+}
+
+}  // namespace
+}  // namespace specext
+
+using namespace specext;
+
+extern "C" {
+
+int specext_calib_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+  if (!src || bytes == 0) return SPECEXT_ERR_INVALID_ARG;
+  constexpr size_t kGranule = static_cast<size_t>(kStreamThreads) * kStreamUnroll * 16;      // 32 KiB
+  if ((reinterpret_cast<uintptr_t>(src) & 15u) || bytes % kGranule != 0) return SPECEXT_ERR_UNSUPPORTED;
+  const size_t blocks = bytes / kGranule;
+  const unsigned grid = static_cast<unsigned>(blocks < 256 * 16 ? blocks : 256 * 16);
+  calib_stream_kernel<<<grid, kStreamThreads, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const uintx4*>(src),
+                                                                                     bytes / 16, sink);
+  return hipGetLastError() == hipSuccess ? SPECEXT_OK : SPECEXT_ERR_LAUNCH_FAILED;
+}
+
+int64_t specext_calib_mfma(int32_t iters, int32_t tile, int32_t workgroups, float* sink, void* stream) {
+  if (iters <= 0 || workgroups <= 0 || (tile != 32 && tile != 16)) return SPECEXT_ERR_INVALID_ARG;
+  if (iters > (1 << 24) || workgroups > (1 << 16)) return SPECEXT_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (tile == 32) calib_mfma_kernel<true><<<workgroups, 256, 0, s>>>(iters, sink);
+  else calib_mfma_kernel<false><<<workgroups, 256, 0, s>>>(iters, sink);
+  if (hipGetLastError() != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  // floating-point operations of the launch: workgroups x 4 waves x iters x 16 products
+  const int64_t per_product = tile == 32 ? 2LL * 32 * 32 * 16 : 2LL * 16 * 16 * 32;
+  return static_cast<int64_t>(workgroups) * 4 * iters * 16 * per_product;
+}
+
+}  // extern "C"

@@ -14,6 +14,22 @@ namespace specext {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+// Hand-over between the workgroups that share the rows of one KV head when the tree pass
+// and the merge run as the tail of the prefix kernel: one block per (KV head, row group)
+// in the workspace header.  specext_workspace_init clears the blocks once; every call leaves
+// `done` and `abandon` at zero and `epoch` one higher, so no call depends on what the one
+// before left in `flags`.
+struct SyncBlock {
+  uint32_t epoch;        // calls completed on this block; flag values of the current call are epoch + 1
+  uint32_t done;         // workgroups that have finished (or given up) in the current call
+  uint64_t abandon;      // bit s: the owner of slice s stopped waiting; the last workgroup to finish merges it
+  uint32_t pad[12];
+  uint32_t flags[64];    // flags[s] == epoch + 1: the partial results of prefix split s are in memory
+};
+static_assert(sizeof(SyncBlock) == 320, "SyncBlock layout");
+constexpr int kMaxSyncBlocks = 256;
+constexpr uint64_t kWorkspaceCookie = 0x53504558544e4431ull;   // written by specext_workspace_init
+
 // One verification-attention problem with every default resolved.  Passed to
 // kernels by value.  Rows of a KV head g are numbered m = t * G + hg
 // (t = tree node, hg = query head within the group); the global row id is
@@ -34,12 +50,16 @@ struct AttnParams {
   float* part_ml;      // [S][Hq*T][2]  (running max, running sum) per split
   float* part_o;       // [S][Hq*T][d]  unnormalised partial outputs
   float* chunk_part;   // [Hkv][n_sub][M][2]  (sum of exp2(s - ref), ref) per score block; null unless want_scores
+  SyncBlock* sync;     // [kMaxSyncBlocks] hand-over blocks of the fused tail
+  const uint64_t* cookie;   // kWorkspaceCookie once the workspace was initialised; null = do not check (library-owned memory)
   int32_t Hq, Hkv, G, d, L, T, M;
   int32_t B, C, S, keys_per_split, want_scores;
   int32_t score_gran, n_sub;      // keys per score block (32 on the MFMA path, else B) and their count
   int32_t use_mfma;               // 0 vector-ALU kernel, 1 matrix-core key-split kernel, 2 matrix-core row-split kernel
   int32_t rows_per_group;         // query rows of one KV head that one workgroup covers
   int32_t part_f16;               // part_o [S][rows][d] holds the unnormalised O as fp16 (1: row-split kernel) or fp32 (0)
+  int32_t fused_tail;             // 1: the row-split kernel also runs the tree pass and the merge (no second launch)
+  int32_t spin_limit;             // polls of the arrival counter before a workgroup hands its slice to the last arriver
   int32_t in_dtype, out_dtype;
   float scale_log2;
   int64_t q_st, q_sh, kp_sh, kp_sl, kt_sh, kt_st, o_st, o_sh;

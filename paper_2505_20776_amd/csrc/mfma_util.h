@@ -79,6 +79,33 @@ __device__ __forceinline__ void wait_vmcnt_even(int n) {
   }
 }
 
+// 16 bytes written / read at device scope (two 8-byte relaxed atomics: the accesses go to
+// the point where the compute units of all XCDs agree, past the per-XCD L2 caches, so a
+// workgroup on another XCD reads what was written without cache write-backs or invalidations)
+__device__ __forceinline__ void store_device_scope_16(void* dst, const uintx4 v) {
+  uint64_t* d = static_cast<uint64_t*>(dst);
+  __hip_atomic_store(d, static_cast<uint64_t>(v[0]) | (static_cast<uint64_t>(v[1]) << 32), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(d + 1, static_cast<uint64_t>(v[2]) | (static_cast<uint64_t>(v[3]) << 32), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uintx4 load_device_scope_16(const void* src) {
+  const uint64_t* s = static_cast<const uint64_t*>(src);
+  const uint64_t a = __hip_atomic_load(s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint64_t b = __hip_atomic_load(s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return uintx4{static_cast<uint32_t>(a), static_cast<uint32_t>(a >> 32), static_cast<uint32_t>(b),
+                static_cast<uint32_t>(b >> 32)};
+}
+__device__ __forceinline__ void store_device_scope_8(void* dst, const floatx2 v) {
+  __hip_atomic_store(static_cast<uint64_t*>(dst),
+                     static_cast<uint64_t>(__float_as_uint(v[0])) | (static_cast<uint64_t>(__float_as_uint(v[1])) << 32),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ floatx2 load_device_scope_8(const void* src) {
+  const uint64_t a = __hip_atomic_load(static_cast<const uint64_t*>(src), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return floatx2{__uint_as_float(static_cast<uint32_t>(a)), __uint_as_float(static_cast<uint32_t>(a >> 32))};
+}
+
 // workgroup barrier that the compiler may not move LDS accesses across
 __device__ __forceinline__ void lds_barrier() {
   asm volatile("" ::: "memory");

@@ -28,6 +28,7 @@
 //   ds_read_b64_tr_b16), B = P^T taken straight from the S^T accumulator registers:
 //   the key order that layout implies is used as the contraction order and V is
 //   fetched in that same order, so P never moves between lanes.
+#include "merge_tail.h"
 #include "mfma_util.h"
 
 namespace specext {
@@ -52,7 +53,8 @@ constexpr int kRingBytes = 2 * kRing * kTileBytes;
 // (rows padded to 264 B so that the 8-byte column writes fall into distinct banks).
 constexpr int kPatchStride = kRowBytes + 8;
 constexpr int kPrivBytes = 32 * kPatchStride;
-constexpr int lds_bytes(int waves) { return kRingBytes + waves * kPrivBytes; }
+// Behind those, the area of the fused tree-pass / merge tail (parent[], control words, tree slots).
+constexpr int lds_bytes(int waves) { return kRingBytes + waves * kPrivBytes + tail_private_bytes(waves * 64); }
 static_assert(kStages >= 2 && lds_bytes(8) <= 160 * 1024, "rings and private areas must fit the 160 KB of LDS");
 
 template <int I>
@@ -75,6 +77,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c32 = lane & 31;
   const int hf = lane >> 5;
+#ifdef SPECEXT_TAIL_STAMPS
+  const unsigned long long stamp_start = wall_clock64();
+#endif
 
   const int split = blockIdx.x;
   const int g = blockIdx.y;
@@ -167,6 +172,25 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       const unsigned voff = static_cast<unsigned>((tq * p.q_st + hq * p.q_sh) * 2) + ((ld_slot ^ (r & 15)) << 4);
       load_to_lds_16(priv_lds + u * 1024, voff, qbase);
     }
+  }
+  // Fused tail: parent[] goes to the tail's LDS area with one direct load per wave (lane i
+  // of wave w fills entry 64 w + i; lanes past the tree re-read its last entry), and the
+  // hand-over block's epoch and the workspace's initialisation mark are read now, long
+  // before the tail needs them.  These loads are older than those of the next stages, so
+  // the counted waits below stay valid (they only ever wait for more).
+  unsigned char* tail_priv = lds + kRingBytes + WAVES * kPrivBytes;
+  uint32_t epoch = 0;
+  bool cookie_ok = true;
+  if (p.fused_tail) {
+    if (wave * 64 < p.T) {
+      const unsigned tail_lds = kring_lds + kRingBytes + WAVES * kPrivBytes;
+      const unsigned voff = static_cast<unsigned>(min(static_cast<int>(threadIdx.x), p.T - 1)) * 4u;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                   :: "s"(tail_lds + wave * 256), "v"(voff), "s"(p.parent) : "memory", "m0");
+    }
+    if (threadIdx.x < 16) reinterpret_cast<int*>(tail_priv + kTailCtlOff)[threadIdx.x] = 0;
+    epoch = p.sync[blockIdx.z * p.Hkv + g].epoch;
+    cookie_ok = p.cookie == nullptr || *p.cookie == kWorkspaceCookie;
   }
   static_for<1, kStages - 1>([&](auto u_c) {
     constexpr int u = decltype(u_c)::value;
@@ -345,15 +369,32 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     const int row = 4 * it + (lane >> 4);
     const uintx2* src = reinterpret_cast<const uintx2*>(priv + row * kPatchStride + 16 * (lane & 15));
     const uintx2 a = src[0], b = src[1];
-    // non-temporal: the partials leave the L2 as they are written instead of waiting there
-    // for the write-back at the end of the kernel (measured: 1.4 us per launch)
-    if (row < rows_here)
-      __builtin_nontemporal_store(uintx4{a[0], a[1], b[0], b[1]},
-                                  reinterpret_cast<uintx4*>(part_h + (slot0 + row) * kD + 8 * (lane & 15)));
+    // Separate merge launch: non-temporal stores, so that the partials leave the L2 as they are
+    // written instead of waiting there for the write-back at the end of the kernel (measured:
+    // 1.4 us per launch).  Merge in this launch: device-scope stores, which the workgroups of
+    // the other XCDs can read back without cache maintenance.
+    if (row < rows_here) {
+      const uintx4 v = {a[0], a[1], b[0], b[1]};
+      uint16_t* dst = part_h + (slot0 + row) * kD + 8 * (lane & 15);
+      if (p.fused_tail) store_device_scope_16(dst, v);
+      else __builtin_nontemporal_store(v, reinterpret_cast<uintx4*>(dst));
+    }
   }
   if (hf == 0 && m < p.M) {
-    __builtin_nontemporal_store(floatx2{ref * c + static_cast<float>(row_exp), l_tot * row_scale},
-                                reinterpret_cast<floatx2*>(p.part_ml + (slot0 + c32) * 2));
+    const floatx2 v = {ref * c + static_cast<float>(row_exp), l_tot * row_scale};
+    float* dst = p.part_ml + (slot0 + c32) * 2;
+    if (p.fused_tail) store_device_scope_8(dst, v);
+    else __builtin_nontemporal_store(v, reinterpret_cast<floatx2*>(dst));
+  }
+  // tree pass and merge in the same launch: this workgroup merges its slice of the head's rows
+  if (p.fused_tail) {
+#ifdef SPECEXT_TAIL_STAMPS
+    if (threadIdx.x == 0)
+      (reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(p.part_o) +
+                                             static_cast<size_t>(p.S) * p.Hq * p.T * kD * 2) +
+       ((blockIdx.z * p.Hkv + g) * p.S + split) * 8)[0] = stamp_start;
+#endif
+    tree_merge_tail<WAVES * 64>(p, lds, tail_priv, split, g, blockIdx.z, WAVES * 32, epoch, cookie_ok);
   }
 }
 

@@ -43,6 +43,7 @@ def make_buffers(*, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, 
     if nbytes == 0:
         raise ValueError("descriptor rejected by specext_workspace_bytes")
     ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    sx.workspace_init(ws)
     out = torch.empty((n_tree, n_q_heads, head_dim), dtype=torch.bfloat16 if odt == "bf16" else torch.float32,
                       device=device)
     lse = torch.empty((n_q_heads, n_tree), dtype=torch.float32, device=device)

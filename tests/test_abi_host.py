@@ -70,7 +70,7 @@ def test_workspace_and_splits(sx):
     ("struct_size", 4, -1), ("n_q_heads", 0, -1), ("n_kv_heads", 5, -1), ("prefix_len", -1, -1),
     ("n_tree", 0, -1), ("chunk_size", 0, -1), ("num_splits", -2, -1), ("softmax_scale", -1.0, -1),
     ("dtype", 7, -2), ("head_dim", 96, -2), ("n_tree", 129, -2), ("num_splits", 257, -2),
-    ("q_stride_h", 12, -2), ("kp_stride_l", 64, -1), ("reserved", 1, -1), ("flags", 4, -1),
+    ("q_stride_h", 12, -2), ("kp_stride_l", 64, -1), ("reserved", 1, -1), ("flags", 16, -1),
 ])
 def test_bad_descriptor_is_rejected(sx, field, value, status):
     d = _good(sx)

@@ -94,9 +94,9 @@ typedef struct specext_desc {
   int32_t n_q_heads;      /* Hq */
   int32_t n_kv_heads;     /* Hkv, must divide Hq; query head h reads KV head h / G */
   int32_t head_dim;       /* d: 64 or 128 */
-  int32_t prefix_len;     /* L >= 0 cached positions */
+  int32_t prefix_len;     /* 0 <= L <= 2^30 cached positions */
   int32_t n_tree;         /* T in [1, SPECEXT_MAX_TREE] */
-  int32_t chunk_size;     /* B > 0; only read when want_scores != 0.  The bf16 fast path
+  int32_t chunk_size;     /* 0 < B <= 2^24; only read when want_scores != 0.  The bf16 fast path
                              needs B to be a multiple of 32; other values take the generic kernel. */
   int32_t want_scores;    /* != 0: also leave per-chunk partial sums in the workspace */
   int32_t num_splits;     /* pieces the prefix is cut into; 0 = choose automatically */
@@ -306,6 +306,24 @@ int specext_commit_tree_kv(const void* k_tree, const void* v_tree, void* k_cache
  */
 int specext_chunk_scores_accepted(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
                                   const int32_t* path, const int32_t* n_accept, float* scores, void* stream);
+
+/*
+ * specext_chunk_scores for one tree row followed by specext_select_chunks over that
+ * row's scores (Sec. 3.2.1; SelectChunks of Alg. 1), in one launch when there are at most
+ * 1024 chunks (two launches beyond that).  Same scores and the same selection, bit for
+ * bit, as the two calls.
+ *
+ *   desc, workspace   as for specext_chunk_scores
+ *   score_row         the tree row when path is NULL (0 <= score_row < n_tree); else the
+ *                     row is path[*n_accept - 1] read on the device (row 0 when nothing
+ *                     was accepted), path and n_accept as written by specext_accept_greedy
+ *   k, idx_out, n_out as for specext_select_chunks
+ *   scores            fp32 [C] that also receives the scores, or NULL (allowed up to
+ *                     1024 chunks; beyond that SPECEXT_ERR_INVALID_ARG)
+ */
+int specext_chunk_scores_select(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                                int32_t score_row, const int32_t* path, const int32_t* n_accept, int32_t k,
+                                float* scores, int32_t* idx_out, int32_t* n_out, void* stream);
 
 /*
  * Prefill attention (Sec. 3.1: FlashAttention is applied to the prefill stage of the

@@ -34,7 +34,7 @@ EXPORTED = ("specext_strerror", "specext_workspace_bytes", "specext_num_splits",
             "specext_commit_tree_kv", "specext_chunk_scores_accepted", "specext_materialized_bytes",
             "specext_materialized_ld", "specext_attn_materialized", "specext_chunk_scores_materialized",
             "specext_prefill_attn", "specext_verify_attn_static", "specext_workspace_init",
-            "specext_calib_stream_read", "specext_calib_mfma")
+            "specext_calib_stream_read", "specext_calib_mfma", "specext_chunk_scores_select")
 
 
 class SpecextError(RuntimeError):
@@ -108,6 +108,8 @@ def load_library() -> ctypes.CDLL:
     lib.specext_prefill_attn.restype = ctypes.c_int
     lib.specext_prefill_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, ctypes.c_float,
                                          i64, i64, i64, i64, i64, i64, vp]
+    lib.specext_chunk_scores_select.restype = ctypes.c_int
+    lib.specext_chunk_scores_select.argtypes = [dp, vp, sz, i32, vp, vp, i32, vp, vp, vp, vp]
     lib.specext_calib_stream_read.restype = ctypes.c_int
     lib.specext_calib_stream_read.argtypes = [vp, sz, vp, vp]
     lib.specext_calib_mfma.restype = ctypes.c_int64
@@ -328,4 +330,16 @@ def calib_mfma(iters: int, tile: int = 32, workgroups: int = 512, sink=None, str
                                                     _stream(stream)))
     if check and rc < 0:
         _check(rc, "specext_calib_mfma")
+    return rc
+
+
+def chunk_scores_select(desc, workspace, score_row: int, k: int, idx_out, n_out, scores=None, path=None, n_accept=None,
+                        workspace_nbytes: Optional[int] = None, stream=None, check: bool = True) -> int:
+    if workspace_nbytes is None:
+        workspace_nbytes = workspace.numel() * workspace.element_size()
+    rc = load_library().specext_chunk_scores_select(ctypes.byref(desc), _ptr(workspace), workspace_nbytes,
+                                                    int(score_row), _ptr(path), _ptr(n_accept), int(k), _ptr(scores),
+                                                    _ptr(idx_out), _ptr(n_out), _stream(stream))
+    if check:
+        _check(rc, "specext_chunk_scores_select")
     return rc

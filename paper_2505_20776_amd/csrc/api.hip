@@ -62,6 +62,8 @@ int resolve(const specext_desc* d, AttnParams* p) {
     return SPECEXT_ERR_INVALID_ARG;
   if (d->n_q_heads % d->n_kv_heads != 0) return SPECEXT_ERR_INVALID_ARG;
   if (d->want_scores && d->chunk_size <= 0) return SPECEXT_ERR_INVALID_ARG;
+  // bounds that keep the 32-bit length arithmetic below exact (rounding a length up to a chunk or a split unit)
+  if (d->prefix_len > (1 << 30) || (d->want_scores && d->chunk_size > (1 << 24))) return SPECEXT_ERR_UNSUPPORTED;
   if (!(d->softmax_scale >= 0.f) || std::isinf(d->softmax_scale)) return SPECEXT_ERR_INVALID_ARG;
   if (d->reserved != 0 || (d->flags & ~(SPECEXT_FLAG_VALU_PREFIX | SPECEXT_FLAG_PREFIX_ONLY | SPECEXT_FLAG_FUSED_MERGE |
                                        SPECEXT_FLAG_SHORT_WAIT)) != 0) return SPECEXT_ERR_INVALID_ARG;
@@ -381,6 +383,37 @@ int specext_chunk_scores_accepted(const specext_desc* desc, const void* workspac
   bind_workspace(&p, w, const_cast<void*>(workspace));
   if (launch_chunk_scores(p, 0, path, n_accept, scores, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SPECEXT_ERR_LAUNCH_FAILED;
+  return SPECEXT_OK;
+}
+
+int specext_chunk_scores_select(const specext_desc* desc, const void* workspace, size_t workspace_bytes,
+                                int32_t score_row, const int32_t* path, const int32_t* n_accept, int32_t k,
+                                float* scores, int32_t* idx_out, int32_t* n_out, void* stream) {
+  AttnParams p;
+  const int rc = resolve(desc, &p);
+  if (rc != SPECEXT_OK) return rc;
+  if (!workspace || !n_out || !p.want_scores || p.C <= 0 || k < 0 || (k > 0 && !idx_out)) return SPECEXT_ERR_INVALID_ARG;
+  if ((path == nullptr) != (n_accept == nullptr)) return SPECEXT_ERR_INVALID_ARG;
+  if (!path && (score_row < 0 || score_row >= p.T)) return SPECEXT_ERR_INVALID_ARG;
+  if (p.C > 65536) return SPECEXT_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 || (reinterpret_cast<uintptr_t>(scores) & 3u) ||
+      (reinterpret_cast<uintptr_t>(path) & 3u) || (reinterpret_cast<uintptr_t>(n_accept) & 3u) ||
+      (reinterpret_cast<uintptr_t>(idx_out) & 3u) || (reinterpret_cast<uintptr_t>(n_out) & 3u))
+    return SPECEXT_ERR_UNSUPPORTED;
+  // beyond what one workgroup ranks, the two steps run as two launches and need the scores in memory
+  if (p.C > 1024 && !scores) return SPECEXT_ERR_INVALID_ARG;
+  const WorkspaceLayout w = layout_of(p);
+  if (workspace_bytes < w.total) return SPECEXT_ERR_WORKSPACE_TOO_SMALL;
+  bind_workspace(&p, w, const_cast<void*>(workspace));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int32_t row = path ? 0 : score_row;
+  if (p.C <= 1024) {
+    if (launch_score_select(p, row, path, n_accept, k, scores, idx_out, n_out, s) != hipSuccess)
+      return SPECEXT_ERR_LAUNCH_FAILED;
+    return SPECEXT_OK;
+  }
+  if (launch_chunk_scores(p, row, path, n_accept, scores, s) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
+  if (launch_select_chunks(scores, p.C, k, idx_out, n_out, s) != hipSuccess) return SPECEXT_ERR_LAUNCH_FAILED;
   return SPECEXT_OK;
 }
 

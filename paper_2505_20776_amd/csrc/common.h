@@ -102,6 +102,10 @@ hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream);
 // row_path[*row_count - 1] (row 0 when *row_count <= 0)
 hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, const int32_t* row_path,
                                const int32_t* row_count, float* scores, hipStream_t stream);
+// chunk scores of one row and their top-k in one launch; needs p.C <= 1024
+hipError_t launch_score_select(const AttnParams& p, int32_t score_row, const int32_t* row_path,
+                               const int32_t* row_count, int32_t k, float* scores, int32_t* idx_out, int32_t* n_out,
+                               hipStream_t stream);
 hipError_t launch_accept_greedy(const int32_t* parent, const int32_t* draft_token, const int32_t* target_token,
                                 const int32_t* first_target, int32_t n_tree, int32_t* path_out,
                                 int32_t* n_accept_out, int32_t* next_token_out, hipStream_t stream);

@@ -318,12 +318,13 @@ __device__ __forceinline__ void tree_merge_tail(const AttnParams& p, unsigned ch
     for (int r0 = 0; r0 < n; r0 += Rb) {
       const bool row_ok = r0 + r_in < n;
       const int m = lo + min(r0 + r_in, n - 1);          // groups past the slice's end repeat its last row and store nothing
-      if (!(tree_ready && r0 == 0) && k < Rb) {
-        TreeLoads tl;
-        tree_request(m, tl);
-        tree_finish(tl, tree_slot + k * kSlot);
-      }
+      // a group that also has the tree part of a row requests that first and finishes it
+      // after its share of the partials, so that all its loads are in flight together
+      const bool tree_here = !(tree_ready && r0 == 0) && k < Rb;
+      TreeLoads tl;
+      if (tree_here) tree_request(m, tl);
       if (j_sub < P) merge_partial(g * p.M + m, part_slot + k * kSlot);
+      if (tree_here) tree_finish(tl, tree_slot + k * kSlot);
       tail_barrier();
       if (k < Rb && row_ok) finalize(m);
       tail_barrier();

@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void chunk_scores_kernel(AttnParams p, int fir
   const int c = blockIdx.x * 64 + cl;
   int t = first_row + blockIdx.y;
   if (row_path) {                                // the row comes from the acceptance walk: its last accepted node
-    const int cnt = *row_count;
+    const int cnt = min(*row_count, p.T);            // never past the path array, whatever the count says
     const int node = cnt > 0 ? row_path[cnt - 1] : 0;
     t = (node >= 0 && node < p.T) ? node : 0;
   }
@@ -191,10 +191,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
 // bit of the radix search above.  The output order comes from ballot prefix counts.
 constexpr int kRankMax = 1024;
 
-__global__ __launch_bounds__(kRankMax) void select_rank_kernel(const float* __restrict__ scores, int n, int k,
-                                                              int* __restrict__ idx_out, int* __restrict__ n_out) {
-  __shared__ __attribute__((aligned(16))) uint32_t keys[kRankMax];
-  __shared__ int wave_takes[kRankMax / 64];
+// One workgroup, thread i holding the score of chunk i (threads past n hold nothing): ranks
+// the scores through `keys` / `wave_takes` (LDS) and writes idx_out / n_out.
+__device__ __forceinline__ void rank_and_write(float score, int n, int k, int* __restrict__ idx_out,
+                                               int* __restrict__ n_out, uint32_t* keys, int* wave_takes) {
   const int i = threadIdx.x;
   const int lane = i & 63;
   const int wave = i >> 6;
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kRankMax) void select_rank_kernel(const float* __re
   for (int u = k_eff + i; u < k; u += blockDim.x) idx_out[u] = -1;
   if (k_eff == 0) return;
   // keys are kept >= 1 so that "key - 1" below cannot wrap; padding slots hold 0, below every key
-  const uint32_t mine = i < n ? max(orderable(scores[i]), 1u) : 0u;
+  const uint32_t mine = i < n ? max(orderable(score), 1u) : 0u;
   keys[i] = mine;
   __syncthreads();
   const int n4 = (n + 3) & ~3;                   // blockDim.x is a multiple of 64, so the padding exists
@@ -236,6 +236,60 @@ __global__ __launch_bounds__(kRankMax) void select_rank_kernel(const float* __re
     for (int w = 0; w < wave; ++w) pos += wave_takes[w];
     idx_out[pos] = i;
   }
+}
+
+__global__ __launch_bounds__(kRankMax) void select_rank_kernel(const float* __restrict__ scores, int n, int k,
+                                                              int* __restrict__ idx_out, int* __restrict__ n_out) {
+  __shared__ __attribute__((aligned(16))) uint32_t keys[kRankMax];
+  __shared__ int wave_takes[kRankMax / 64];
+  const int i = threadIdx.x;
+  rank_and_write(i < n ? scores[i] : 0.f, n, k, idx_out, n_out, keys, wave_takes);
+}
+
+// Chunk scores of one tree row and the top-k over them in one launch (at most kRankMax
+// chunks): thread c computes the score of chunk c with the arithmetic of
+// chunk_scores_kernel (four partial sums over the heads h = 0, 1, 2, 3 mod 4, each in
+// ascending h, combined in the same fixed order: the same bits) and the workgroup ranks
+// them as select_rank_kernel does.  scores may be null.
+__global__ __launch_bounds__(kRankMax) void score_select_kernel(AttnParams p, int score_row, const int* row_path,
+                                                               const int* row_count, int k, float* scores,
+                                                               int* __restrict__ idx_out, int* __restrict__ n_out) {
+  __shared__ __attribute__((aligned(16))) uint32_t keys[kRankMax];
+  __shared__ int wave_takes[kRankMax / 64];
+  const int c = threadIdx.x;
+  int t = score_row;
+  if (row_path) {
+    const int cnt = min(*row_count, p.T);
+    const int node = cnt > 0 ? row_path[cnt - 1] : 0;
+    t = (node >= 0 && node < p.T) ? node : 0;
+  }
+  float score = 0.f;
+  if (c < p.C) {
+    const int per_chunk = p.B / p.score_gran;
+    const int sub_lo = c * per_chunk;
+    const int sub_hi = min(sub_lo + per_chunk, p.n_sub);
+    float part[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int h0 = 0; h0 < p.Hq; h0 += 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int h = h0 + u;
+        if (h < p.Hq) {
+          const int g = h / p.G;
+          const int m = t * p.G + (h - g * p.G);
+          const float l2 = p.lse2[g * p.M + m];
+          for (int sb = sub_lo; sb < sub_hi; ++sb) {
+            const float2 cp = *reinterpret_cast<const float2*>(
+                p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sb) * p.M + m) * 2);
+            part[u] += cp.x * exp2f(cp.y - l2);
+          }
+        }
+      }
+    }
+    const int size = min(p.B, p.L - c * p.B);
+    score = (((part[0] + part[1]) + part[2]) + part[3]) / (static_cast<float>(size) * static_cast<float>(p.Hq));
+    if (scores) scores[c] = score;
+  }
+  rank_and_write(score, p.C, k, idx_out, n_out, keys, wave_takes);
 }
 
 // --------------------------------------------------------------------------
@@ -334,6 +388,15 @@ hipError_t launch_chunk_scores(const AttnParams& p, int32_t score_row, const int
   const int rows = (score_row < 0 && !row_path) ? p.T : 1;
   dim3 grid((p.C + 63) / 64, rows);
   chunk_scores_kernel<<<grid, dim3(256), 0, stream>>>(p, score_row < 0 ? 0 : score_row, row_path, row_count, scores);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_select(const AttnParams& p, int32_t score_row, const int32_t* row_path,
+                               const int32_t* row_count, int32_t k, float* scores, int32_t* idx_out, int32_t* n_out,
+                               hipStream_t stream) {
+  if (p.C > kRankMax) return hipErrorInvalidValue;
+  const int threads = ((p.C + 63) / 64) * 64;
+  score_select_kernel<<<dim3(1), dim3(threads), 0, stream>>>(p, score_row, row_path, row_count, k, scores, idx_out, n_out);
   return hipGetLastError();
 }
 

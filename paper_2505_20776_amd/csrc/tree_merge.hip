@@ -12,7 +12,7 @@
 // The prefix kernels leave one partial per (split, row): (max, sum) in base-2 units
 // plus the unnormalised output, in fp32 or (row-split matrix-core kernel, which first
 // rescales the triple by a power of two per row) in fp16.
-#include "common.h"
+#include "mfma_util.h"
 
 namespace specext {
 namespace {
@@ -20,8 +20,6 @@ namespace {
 constexpr int kWavesPerBlock = 1;             // small workgroups: the rows spread over every compute unit
 constexpr int kRowsPerWave = 4;
 constexpr int kRowsPerBlock = kWavesPerBlock * kRowsPerWave;
-
-typedef __attribute__((ext_vector_type(2))) _Float16 halfx2;
 
 // N consecutive values starting at element `off` of a bf16 or fp32 array, as fp32
 template <int N, bool BF16>
@@ -50,8 +48,6 @@ __device__ __forceinline__ void load_row_part(const void* base, int64_t off, flo
     }
   }
 }
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // value of `v` in lane `src` (any lane of the wave) for every lane
 __device__ __forceinline__ float lane_read(float v, int src) {

@@ -22,6 +22,25 @@ def dtype_code(dtype: str) -> int:
     return {"f32": sx.SPECEXT_F32, "bf16": sx.SPECEXT_BF16}[dtype]
 
 
+GUARD_BYTES = 4096          # sentinel bytes on each side of every buffer a kernel writes
+GUARD_FILL = 0xA5
+
+
+def guarded(shape, dtype: torch.dtype, device="cuda"):
+    """A tensor of `shape` that sits between two sentinel regions of GUARD_BYTES bytes each.
+    Returns (tensor, base); guards_intact(base) tells whether a kernel wrote outside the tensor."""
+    n = 1
+    for x in shape:
+        n *= int(x)
+    nbytes = n * torch.empty((), dtype=dtype).element_size()
+    base = torch.full((nbytes + 2 * GUARD_BYTES,), GUARD_FILL, dtype=torch.uint8, device=device)
+    return base[GUARD_BYTES:GUARD_BYTES + nbytes].view(dtype).view(*shape), base
+
+
+def guards_intact(base: torch.Tensor) -> bool:
+    return bool((base[:GUARD_BYTES] == GUARD_FILL).all()) and bool((base[-GUARD_BYTES:] == GUARD_FILL).all())
+
+
 @dataclass
 class VerifyBuffers:
     desc: sx.specext_desc
@@ -29,6 +48,12 @@ class VerifyBuffers:
     lse: torch.Tensor
     workspace: torch.Tensor
     scores: Optional[torch.Tensor]
+    bases: dict
+
+    def check_guards(self) -> None:
+        """Raises if anything was written in front of or behind workspace, out, lse or scores."""
+        for name, base in self.bases.items():
+            assert guards_intact(base), f"a kernel wrote outside the {name} buffer"
 
 
 def make_buffers(*, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, prefix_len: int, n_tree: int,
@@ -42,16 +67,16 @@ def make_buffers(*, dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, 
     nbytes = sx.workspace_bytes(desc)
     if nbytes == 0:
         raise ValueError("descriptor rejected by specext_workspace_bytes")
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    bases = {}
+    ws, bases["workspace"] = guarded((nbytes,), torch.uint8, device)
     sx.workspace_init(ws)
-    out = torch.empty((n_tree, n_q_heads, head_dim), dtype=torch.bfloat16 if odt == "bf16" else torch.float32,
-                      device=device)
-    lse = torch.empty((n_q_heads, n_tree), dtype=torch.float32, device=device)
+    out, bases["out"] = guarded((n_tree, n_q_heads, head_dim), torch.bfloat16 if odt == "bf16" else torch.float32, device)
+    lse, bases["lse"] = guarded((n_q_heads, n_tree), torch.float32, device)
     scores = None
     if want_scores:
         n_chunks = (prefix_len + chunk_size - 1) // chunk_size
-        scores = torch.empty((n_tree, max(n_chunks, 1)), dtype=torch.float32, device=device)
-    return VerifyBuffers(desc, out, lse, ws, scores)
+        scores, bases["scores"] = guarded((n_tree, max(n_chunks, 1)), torch.float32, device)
+    return VerifyBuffers(desc, out, lse, ws, scores, bases)
 
 
 def run_verify(wl, *, num_splits: int = 0, want_scores: bool = True, out_dtype: Optional[str] = None,
@@ -75,6 +100,7 @@ def run_verify(wl, *, num_splits: int = 0, want_scores: bool = True, out_dtype: 
     if want_scores:
         sx.chunk_scores(buf.desc, buf.workspace, -1, buf.scores)
     torch.cuda.synchronize()
+    buf.check_guards()
     status = int(buf.workspace[:4].view(torch.int32).item())
     return {
         "out": buf.out.float().cpu().numpy(),
@@ -88,10 +114,13 @@ def run_verify(wl, *, num_splits: int = 0, want_scores: bool = True, out_dtype: 
 def run_select(scores_row: np.ndarray, k: int):
     """select_chunks on one row of scores; returns (idx int32 [min(k,C)], n_out, raw idx buffer)."""
     s = torch.from_numpy(np.ascontiguousarray(scores_row, dtype=np.float32)).cuda()
-    idx = torch.full((max(k, 1),), -7, dtype=torch.int32, device="cuda")
-    n_out = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    idx, idx_base = guarded((max(k, 1),), torch.int32)
+    n_out, n_base = guarded((1,), torch.int32)
+    idx.fill_(-7)
+    n_out.fill_(-7)
     sx.select_chunks(s, s.numel(), k, idx, n_out)
     torch.cuda.synchronize()
+    assert guards_intact(idx_base) and guards_intact(n_base), "select_chunks wrote outside idx_out / n_out"
     n = int(n_out.item())
     raw = idx.cpu().numpy()
     return raw[:n].copy(), n, raw[:k].copy()
@@ -105,18 +134,22 @@ def run_gather(k_src: torch.Tensor, v_src: torch.Tensor, idx: np.ndarray, chunk_
     idx_t = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).cuda()
     max_idx = int(len(idx) if max_idx is None else max_idx)
     cap = max_idx * chunk_size
-    k_dst = torch.full((ld, hh, max(cap, 1), d), 77, dtype=k_src.dtype, device="cuda")[:, :, :cap]
-    v_dst = torch.full((ld, hh, max(cap, 1), d), 77, dtype=k_src.dtype, device="cuda")[:, :, :cap]
-    k_dst = k_dst.contiguous()
-    v_dst = v_dst.contiguous()
-    pos = torch.full((max(cap, 1),), -5, dtype=torch.int32, device="cuda")
-    length = torch.full((1,), -5, dtype=torch.int32, device="cuda")
+    k_dst, k_base = guarded((ld, hh, cap, d), k_src.dtype)
+    v_dst, v_base = guarded((ld, hh, cap, d), k_src.dtype)
+    k_dst.fill_(77)
+    v_dst.fill_(77)
+    pos, pos_base = guarded((max(cap, 1),), torch.int32)
+    length, len_base = guarded((1,), torch.int32)
+    pos.fill_(-5)
+    length.fill_(-5)
     n_idx_t = None if n_idx is None else torch.tensor([n_idx], dtype=torch.int32, device="cuda")
     if idx_t.numel() == 0:
         idx_t = torch.zeros(1, dtype=torch.int32, device="cuda")
     sx.gather_draft_kv(k_src, v_src, k_dst, v_dst, idx_t, n_idx_t, max_idx, ld, hh, plen, cap, d, chunk_size,
                        k_src.element_size(), pos, length)
     torch.cuda.synchronize()
+    for name, base in (("k_dst", k_base), ("v_dst", v_base), ("pos_out", pos_base), ("len_out", len_base)):
+        assert guards_intact(base), f"gather_draft_kv wrote outside {name}"
     return k_dst, v_dst, pos.cpu().numpy()[:cap], int(length.item())
 
 

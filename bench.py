@@ -27,11 +27,19 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
-# HBM bytes of one prefix-kernel launch at the default workload (prefix 16384, automatic splits), from the
-# FETCH_SIZE and WRITE_SIZE counter passes summarised in profiles/prefix_rows_kernel_config4_hbm_traffic.md
-# (FETCH_SIZE scaled by 1.9816, WRITE_SIZE by 1.000, the factors a plain copy of known size gives):
-# 70.6 MB fetched + 16.2 MB written.
-MEASURED_TRAFFIC_BYTES = {16384: 70.6e6 + 16.2e6}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "prefix_rows_kernel_config4_hbm_traffic.txt")
+
+
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel at the default workload, from the summary of the latest
+    FETCH_SIZE / WRITE_SIZE counter passes (written by `python -m paper_2505_20776_amd.profile_summary traffic`,
+    which records the commit it was measured at).  None when there is no summary."""
+    try:
+        fields = dict(line.strip().split("=", 1) for line in open(TRAFFIC_FILE) if "=" in line and not line.startswith("#"))
+        return {"bytes": float(fields["traffic_bytes_per_launch"]), "commit": fields.get("commit", "?"),
+                "fetch_bytes": float(fields["fetch_bytes_per_launch"]), "write_bytes": float(fields["write_bytes_per_launch"])}
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def parse_args():
@@ -39,10 +47,13 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", choices=["2", "3", "4", "5wide", "5chain"], default="4",
+    ap.add_argument("--config", choices=["2", "3", "4", "5wide", "5chain", "draft"], default="4",
                     help="numbered workload: 4 (default) = 32 layers at a 16K prefix, the headline metric; 2 / 3 / 5 = "
                          "the single-layer shapes (2K, 8K, 32K-37 with a 128-node wide tree or a 16-node chain), run "
-                         "over enough distinct K/V copies (>= 300 MB) that every launch streams cold")
+                         "over enough distinct K/V copies (>= 300 MB) that every launch streams cold (a second figure, "
+                         "labelled hot, comes from one copy that stays in the caches); draft = the draft model's side "
+                         "(Sec. 3.2.1): one EAGLE-style layer of the same shape over a compacted working cache of "
+                         "2048 tokens")
     ap.add_argument("--kv-heads", type=int, default=8,
                     help="KV heads (8 = Llama-3.1-8B's grouped queries; 32 = multi-head attention as in the "
                          "Vicuna-7B / LongChat-7B targets of the paper)")
@@ -57,6 +68,9 @@ def parse_args():
                          "self-attention of a --prefix token prompt on all layers (Sec. 3.1), its own JSON line")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-calibrate", action="store_true",
+                    help="skip the two calibration kernels (pure HBM read stream, pure bf16 matrix-core loop) whose rates "
+                         "are reported as measured_* next to the published peaks")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle is timed on (32 = the whole step, about 10 s)")
     return ap.parse_args()
 
@@ -84,10 +98,12 @@ def main():
     Hq, Hkv, d = 32, args.kv_heads, 128
     L, B, topk, parent_np = {"2": (2048, 32, 32, config_tree(2)), "3": (8192, 32, 32, config_tree(3)),
                              "4": (16384, 32, 32, config_tree(4)), "5wide": (32768 - 37, 64, 16, config_tree(5, "wide")),
-                             "5chain": (32768 - 37, 64, 16, config_tree(5, "chain"))}[args.config]
+                             "5chain": (32768 - 37, 64, 16, config_tree(5, "chain")),
+                             "draft": (2048, 32, 32, config_tree(2))}[args.config]
     L = args.prefix or L
     T = len(parent_np)
     layer_bytes = 2 * Hkv * L * d * 2
+    single = args.config != "4"
     n_layers = args.layers or (32 if args.config == "4" else -(-300_000_000 // layer_bytes))
     n_chunks = (L + B - 1) // B
 
@@ -128,42 +144,63 @@ def main():
     if materialized:
         mat_ws = torch.empty(sx.materialized_bytes(last.desc), dtype=torch.uint8, device=dev)
 
-    def step():
-        for l in range(n_layers - 1 if materialized else n_layers):
-            buf = last if l == n_layers - 1 else plain
+    def score_select():
+        # chunk scores of the root row and their top-k, one launch (two beyond 1024 chunks)
+        sx.chunk_scores_select(last.desc, last.workspace, 0, topk, idx, n_out, scores=scores)
+
+    def gather():
+        sx.gather_draft_kv(draft_k, draft_v, ck, cv, idx, n_out, topk, 1, Hkv, L, cap, d, B, 2, pos, length)
+
+    def layers(first, count, buffers=None):
+        for l in range(first, first + count):
+            buf = buffers or (last if l == n_layers - 1 else plain)
             sx.verify_attn(buf.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, outs[l], buf.lse, buf.workspace)
+
+    def step():
+        layers(0, n_layers - 1 if materialized else n_layers)
         if materialized:
             l = n_layers - 1
             sx.attn_materialized(last.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, outs[l], last.lse, mat_ws)
             sx.chunk_scores_materialized(last.desc, mat_ws, 0, scores)
+            sx.select_chunks(scores, n_chunks, topk, idx, n_out)
         else:
-            sx.chunk_scores(last.desc, last.workspace, 0, scores)
-        sx.select_chunks(scores, n_chunks, topk, idx, n_out)
-        sx.gather_draft_kv(draft_k, draft_v, ck, cv, idx, n_out, topk, 1, Hkv, L, cap, d, B, 2, pos, length)
-
-    def prefix_only():
-        for l in range(n_layers):
-            sx.verify_attn(only.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, outs[l], only.lse, only.workspace)
+            score_select()
+        gather()
 
     stream = torch.cuda.Stream()
+
+    def graphed(fn):
+        """fn captured once in a HIP graph (or fn itself with --no-graph)."""
+        if args.no_graph:
+            return fn
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            fn()
+        return g.replay
+
+    def event_time_us(run, reps):
+        """Average GPU time of `run` over `reps` back-to-back calls, HIP events on the launch stream."""
+        run()
+        stream.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            run()
+        e1.record(stream)
+        stream.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
     with torch.cuda.stream(stream):
         for _ in range(max(args.warmup, 1)):
             step()
-        prefix_only()
+        layers(0, n_layers, only)
         stream.synchronize()
-        if args.no_graph:
-            run_step, run_prefix = step, prefix_only
-        else:
-            g_step = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_step, stream=stream):
-                step()
-            g_prefix = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_prefix, stream=stream):
-                prefix_only()
-            run_step, run_prefix = g_step.replay, g_prefix.replay
-            for _ in range(2):
-                run_step()
-            stream.synchronize()
+        run_step = graphed(step)
+        run_prefix = graphed(lambda: layers(0, n_layers, only))
+        for _ in range(2):
+            run_step()
+        stream.synchronize()
 
         # ---- timed region: exactly K steps ----
         torch.cuda.synchronize()
@@ -184,23 +221,37 @@ def main():
         per_step = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
 
         # ---- dominant kernel: prefix pass, HIP events on the launch stream ----
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        run_prefix()
-        stream.synchronize()
-        e0.record(stream)
-        for _ in range(args.steps):
-            run_prefix()
-        e1.record(stream)
-        stream.synchronize()
-        prefix_us = e0.elapsed_time(e1) * 1e3 / (args.steps * n_layers)
+        prefix_us = event_time_us(run_prefix, args.steps) / n_layers
+
+        # ---- the retrieval steps on their own (32 calls per graph, so that launch gaps count as they do in a step) ----
+        reps = 32
+        a45_us = event_time_us(graphed(lambda: [score_select() for _ in range(reps)]), 10) / reps
+        a6_us = event_time_us(graphed(lambda: [gather() for _ in range(reps)]), 10) / reps
+
+        # ---- hot figures for the single-layer workloads: one K/V copy, resident in the caches ----
+        hot = None
+        if single:
+            hot_layer_us = event_time_us(graphed(lambda: [layers(0, 1, plain) for _ in range(reps)]), 10) / reps
+            hot_prefix_us = event_time_us(graphed(lambda: [layers(0, 1, only) for _ in range(reps)]), 10) / reps
+            hot = {"label": "hot: one K/V copy re-read from the caches by every launch",
+                   "us_per_layer": round(hot_layer_us, 3), "prefix_us_per_launch": round(hot_prefix_us, 3),
+                   "prefix_GBps": round(layer_bytes / (hot_prefix_us * 1e-6) / 1e9, 1)}
+
+        # ---- measured ceilings of this GPU, same run ----
+        calib = None
+        if not args.no_calibrate:
+            calib = calibrate(sx, torch, stream, event_time_us)
 
     assert int(n_out.item()) == topk and cap - B < int(length.item()) <= cap
 
-    bytes_per_launch = 2 * Hkv * L * d * 2                     # one layer's K and V prefix, bf16
+    bytes_per_launch = layer_bytes                             # one layer's K and V prefix, bf16
     flops_per_launch = 4.0 * d * T * (Hq // Hkv) * Hkv * L     # QK^T and PV, 2 flops per MAC
     achieved_gbs = bytes_per_launch / (prefix_us * 1e-6) / 1e9
+    achieved_tf = flops_per_launch / (prefix_us * 1e-6) / 1e12
     step_us = ms_per_step * 1e3
+    gather_bytes = 2 * 2 * Hkv * cap * d * 2                   # K and V, read + written
+    default_workload = args.config == "4" and L == 16384 and Hkv == 8 and args.num_splits == 0
+    traffic = measured_traffic() if default_workload else None
     result = {
         "metric": "us per verification step (all layers) at 16K prefix" if (args.config == "4" and L == 16384 and Hkv == 8)
                   else f"us per verification step ({n_layers} layers) at prefix {L}",
@@ -217,7 +268,10 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"config {args.config}: {n_layers} layers x (Hq=32, Hkv={Hkv}, d=128) bf16, prefix {L}, {T}-node tree, "
-                        f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x{Hkv}x{cap}x128",
+                        f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x{Hkv}x{cap}x128"
+                        + (" (every layer its own K/V copy: cold)" if single else ""),
+            "arithmetic": "bf16 inputs, fp32 accumulation on the matrix cores; split partials cross HBM as fp16 "
+                          "after a per-row power-of-two rescale",
             "us_per_layer": round(step_us / n_layers, 2),
             "step_us_median": round(per_step[len(per_step) // 2], 2),
             "step_us_min": round(per_step[0], 2),
@@ -226,6 +280,12 @@ def main():
             "last_layer": args.last_layer,
             "step_hbm_GBps": round(n_layers * bytes_per_launch / (step_us * 1e-6) / 1e9, 1),
             "step_mfma_TFLOPs": round(n_layers * flops_per_launch / (step_us * 1e-6) / 1e12, 1),
+            "a1_prefix_us_per_layer": round(prefix_us, 3),
+            "a2a3_tree_merge_us_per_layer": round((step_us - a45_us - a6_us) / n_layers - prefix_us, 3),
+            "a4a5_scores_select_us": round(a45_us, 3),
+            "a6_gather_us": round(a6_us, 3),
+            "gather_GBps": round(gather_bytes / (a6_us * 1e-6) / 1e9, 1),
+            "gather_copy_frac": round(gather_bytes / (a6_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
         },
         "roofline": {
             "kernel": ("prefix_rows_kernel" if T * (Hq // Hkv) > 32 else "prefix_mfma_kernel") +
@@ -235,22 +295,58 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(L) if (args.num_splits == 0 and args.config == "4" and Hkv == 8) else None,
+            "traffic": traffic["bytes"] if traffic else None,
             "algorithmic_bytes": bytes_per_launch,
             "us_per_launch": round(prefix_us, 3),
-            "mfma_TFLOPs": round(flops_per_launch / (prefix_us * 1e-6) / 1e12, 1),
-            "mfma_frac": round(flops_per_launch / (prefix_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "mfma_TFLOPs": round(achieved_tf, 1),
+            "mfma_frac": round(achieved_tf / MFMA_BF16_PEAK_TFLOPS, 4),
         },
     }
+    rf = result["roofline"]
+    if traffic:
+        rf.update({"traffic_over_algorithmic": round(traffic["bytes"] / bytes_per_launch, 3),
+                   "traffic_fetch_bytes": traffic["fetch_bytes"], "traffic_write_bytes": traffic["write_bytes"],
+                   "traffic_measured_at_commit": traffic["commit"]})
+    if hot:
+        result["config"]["hot"] = hot
+    if calib:
+        rf.update({"measured_hbm_GBps": calib["hbm_GBps"], "measured_mfma_TFLOPs": calib["mfma_TFLOPs"],
+                   "frac_of_measured": round(achieved_gbs / calib["hbm_GBps"], 4),
+                   "mfma_frac_of_measured": round(achieved_tf / calib["mfma_TFLOPs"], 4),
+                   # the share of each measured ceiling the kernel uses; on this part the two draw on one power
+                   # budget, so their sum (not either alone) says how close the kernel is to what the chip gives
+                   "sum_of_measured_fracs": round(achieved_gbs / calib["hbm_GBps"] + achieved_tf / calib["mfma_TFLOPs"], 4),
+                   "calibration": calib["how"]})
+        result["config"]["gather_copy_frac_of_measured"] = round(gather_bytes / (a6_us * 1e-6) / 1e9 / calib["hbm_GBps"], 4)
 
     if T * (Hq // Hkv) * 1.0 > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
         # more flops per K/V byte than the ridge point: the matrix roof is the binding one
-        rf = result["roofline"]
         rf.update({"bound": "mfma", "achieved": rf["mfma_TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                    "frac": rf["mfma_frac"], "hbm_GBps": round(achieved_gbs, 1)})
+        if calib:
+            rf["frac_of_measured"] = rf["mfma_frac_of_measured"]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, n_layers, L, B, topk)
     print(json.dumps(result))
+
+
+def calibrate(sx, torch, stream, event_time_us):
+    """What this GPU sustains: a pure HBM read stream over 2 GiB (eight times the last-level cache) and a pure
+    dense bf16 matrix-core loop, both from the library's calibration kernels, timed like everything else here."""
+    nbytes = 2 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    buf.fill_(1)
+    t_read = event_time_us(lambda: sx.calib_stream_read(buf, nbytes), 10)
+    del buf
+    flops = [0]
+
+    def mfma():
+        flops[0] = sx.calib_mfma(20000, 32, 512)
+
+    t_mfma = event_time_us(mfma, 3)
+    return {"hbm_GBps": round(nbytes / (t_read * 1e-6) / 1e9, 1), "mfma_TFLOPs": round(flops[0] / (t_mfma * 1e-6) / 1e12, 1),
+            "how": "specext_calib_stream_read over 2 GiB x 10; specext_calib_mfma (v_mfma_f32_32x32x16_bf16 only, "
+                   "2 waves per SIMD) 12 ms x 3; same process, same stream"}
 
 
 def bench_prefill(args):
@@ -335,8 +431,8 @@ def cpu_baseline(args, n_layers, L, B, topk):
     t_attn = 0.0
     wl = None
     for l in range(sample_layers):
-        cfg = int(args.config[0])
-        wl = config_workload(cfg, item=l, prefix_len=L, variant=args.config[1:])
+        cfg = 2 if args.config == "draft" else int(args.config[0])
+        wl = config_workload(cfg, item=l, prefix_len=L, variant="" if args.config == "draft" else args.config[1:])
         t0 = time.perf_counter()
         orc.verify_attention(wl.q, wl.k_prefix, wl.v_prefix, wl.k_tree, wl.v_tree, wl.parent)
         t_attn += time.perf_counter() - t0

@@ -191,6 +191,59 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
 // bit of the radix search above.  The output order comes from ballot prefix counts.
 constexpr int kRankMax = 1024;
 
+// One workgroup (blockDim.x a multiple of 256, at least n threads), thread i holding the score
+// of chunk i.  The key of the k-th largest score is found a byte at a time from the top:
+// a 256-bin histogram (LDS atomics) of the keys that match the bytes fixed so far, a
+// suffix scan over the bins, and the bin that holds the k-th key fixes the next byte - four
+// rounds instead of one compare of every key with every other.  Keys above the threshold
+// are all taken; of the keys equal to it the lowest-indexed ones fill what is left; two
+// block scans in index order give the ascending output.
+struct RadixLds {
+  int hist[256];
+  int wave_sums[kSelThreads / 64];
+  int sel_bin, sel_need;
+};
+
+__device__ __forceinline__ void radix_select_and_write(float score, int n, int k, int* __restrict__ idx_out,
+                                                       int* __restrict__ n_out, RadixLds& sh) {
+  const int i = threadIdx.x;
+  const int k_eff = min(k, n);
+  if (i == 0) *n_out = k_eff;
+  for (int u = k_eff + i; u < k; u += blockDim.x) idx_out[u] = -1;
+  if (k_eff == 0) return;
+  const bool live = i < n;
+  const uint32_t key = live ? orderable(score) : 0u;
+  uint32_t prefix = 0;           // the bytes of the threshold fixed so far (higher bytes first)
+  int need = k_eff;              // keys still to take among those that match `prefix` in the fixed bytes
+#pragma unroll
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (i < 256) sh.hist[i] = 0;
+    __syncthreads();
+    const bool match = live && (shift == 24 || (key >> (shift + 8)) == (prefix >> (shift + 8)));
+    if (match) atomicAdd(&sh.hist[(key >> shift) & 255u], 1);
+    __syncthreads();
+    // thread t < 256 looks at bin 255 - t: `above` = keys in higher bins
+    const int mine = i < 256 ? sh.hist[255 - i] : 0;
+    int total;
+    const int above = block_exclusive_scan(mine, sh.wave_sums, total);
+    if (i < 256 && above < need && need <= above + mine) {
+      sh.sel_bin = 255 - i;
+      sh.sel_need = need - above;
+    }
+    __syncthreads();
+    prefix |= static_cast<uint32_t>(sh.sel_bin) << shift;
+    need = sh.sel_need;
+  }
+  // prefix is the k-th largest key; `need` of the keys equal to it are taken, lowest index first
+  const int is_tie = (live && key == prefix) ? 1 : 0;
+  int tie_total;
+  const int tie_rank = block_exclusive_scan(is_tie, sh.wave_sums, tie_total);
+  const int take = (live && key > prefix) ? 1 : (is_tie & (tie_rank < need ? 1 : 0));
+  int take_total;
+  const int pos = block_exclusive_scan(take, sh.wave_sums, take_total);
+  if (take) idx_out[pos] = i;
+}
+
 // One workgroup, thread i holding the score of chunk i (threads past n hold nothing): ranks
 // the scores through `keys` / `wave_takes` (LDS) and writes idx_out / n_out.
 __device__ __forceinline__ void rank_and_write(float score, int n, int k, int* __restrict__ idx_out,
@@ -247,49 +300,68 @@ __global__ __launch_bounds__(kRankMax) void select_rank_kernel(const float* __re
 }
 
 // Chunk scores of one tree row and the top-k over them in one launch (at most kRankMax
-// chunks): thread c computes the score of chunk c with the arithmetic of
-// chunk_scores_kernel (four partial sums over the heads h = 0, 1, 2, 3 mod 4, each in
-// ascending h, combined in the same fixed order: the same bits) and the workgroup ranks
-// them as select_rank_kernel does.  scores may be null.
+// chunks, 1024 threads).  Scores with the arithmetic of chunk_scores_kernel - the heads of
+// a chunk are dealt to four threads (head h to thread h mod 4), each adds its heads in
+// ascending order, the four sums are combined in the same fixed order: the same bits -
+// a quarter of the threads' number of chunks per pass, all loads of a thread requested
+// before the first is used; then the byte-wise selection above.  scores may be null.
 __global__ __launch_bounds__(kRankMax) void score_select_kernel(AttnParams p, int score_row, const int* row_path,
                                                                const int* row_count, int k, float* scores,
                                                                int* __restrict__ idx_out, int* __restrict__ n_out) {
-  __shared__ __attribute__((aligned(16))) uint32_t keys[kRankMax];
-  __shared__ int wave_takes[kRankMax / 64];
-  const int c = threadIdx.x;
+  __shared__ RadixLds radix;
+  __shared__ float partial[kRankMax][4];
   int t = score_row;
   if (row_path) {
     const int cnt = min(*row_count, p.T);
     const int node = cnt > 0 ? row_path[cnt - 1] : 0;
     t = (node >= 0 && node < p.T) ? node : 0;
   }
-  float score = 0.f;
-  if (c < p.C) {
-    const int per_chunk = p.B / p.score_gran;
-    const int sub_lo = c * per_chunk;
-    const int sub_hi = min(sub_lo + per_chunk, p.n_sub);
-    float part[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int h0 = 0; h0 < p.Hq; h0 += 4) {
+  const int part = threadIdx.x & 3;
+  const int per_chunk = p.B / p.score_gran;
+  constexpr int kHeadsAtOnce = 8;                // heads of one thread whose loads are in flight together
+  const int chunks_per_pass = blockDim.x / 4;
+  for (int c0 = 0; c0 < p.C; c0 += chunks_per_pass) {
+    const int c = c0 + (threadIdx.x >> 2);
+    float acc = 0.f;
+    if (c < p.C) {
+      const int sub_lo = c * per_chunk;
+      const int sub_hi = min(sub_lo + per_chunk, p.n_sub);
+      for (int hb = part; hb < p.Hq; hb += 4 * kHeadsAtOnce) {
+        float l2[kHeadsAtOnce];
+        float2 first[kHeadsAtOnce];
+        const float* src[kHeadsAtOnce];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int h = h0 + u;
-        if (h < p.Hq) {
+        for (int u = 0; u < kHeadsAtOnce; ++u) {
+          const int h = min(hb + 4 * u, p.Hq - 1);               // heads past the end re-read the last one, unused
           const int g = h / p.G;
           const int m = t * p.G + (h - g * p.G);
-          const float l2 = p.lse2[g * p.M + m];
-          for (int sb = sub_lo; sb < sub_hi; ++sb) {
-            const float2 cp = *reinterpret_cast<const float2*>(
-                p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sb) * p.M + m) * 2);
-            part[u] += cp.x * exp2f(cp.y - l2);
+          l2[u] = p.lse2[g * p.M + m];
+          src[u] = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sub_lo) * p.M + m) * 2;
+          first[u] = *reinterpret_cast<const float2*>(src[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kHeadsAtOnce; ++u) {
+          if (hb + 4 * u < p.Hq) {
+            acc += first[u].x * exp2f(first[u].y - l2[u]);
+            for (int sb = sub_lo + 1; sb < sub_hi; ++sb) {
+              const float2 cp = *reinterpret_cast<const float2*>(src[u] + static_cast<int64_t>(sb - sub_lo) * p.M * 2);
+              acc += cp.x * exp2f(cp.y - l2[u]);
+            }
           }
         }
       }
     }
+    if (c < p.C) partial[c][part] = acc;
+  }
+  __syncthreads();
+  const int c = threadIdx.x;
+  float score = 0.f;
+  if (c < p.C) {
     const int size = min(p.B, p.L - c * p.B);
-    score = (((part[0] + part[1]) + part[2]) + part[3]) / (static_cast<float>(size) * static_cast<float>(p.Hq));
+    score = (((partial[c][0] + partial[c][1]) + partial[c][2]) + partial[c][3]) / (static_cast<float>(size) * static_cast<float>(p.Hq));
     if (scores) scores[c] = score;
   }
-  rank_and_write(score, p.C, k, idx_out, n_out, keys, wave_takes);
+  radix_select_and_write(score, p.C, k, idx_out, n_out, radix);
 }
 
 // --------------------------------------------------------------------------
@@ -395,7 +467,7 @@ hipError_t launch_score_select(const AttnParams& p, int32_t score_row, const int
                                const int32_t* row_count, int32_t k, float* scores, int32_t* idx_out, int32_t* n_out,
                                hipStream_t stream) {
   if (p.C > kRankMax) return hipErrorInvalidValue;
-  const int threads = ((p.C + 63) / 64) * 64;
+  const int threads = p.C <= 256 ? 256 : ((p.C + 255) / 256) * 256;       // one key per thread, all 256 bins covered
   score_select_kernel<<<dim3(1), dim3(threads), 0, stream>>>(p, score_row, row_path, row_count, k, scores, idx_out, n_out);
   return hipGetLastError();
 }

@@ -68,6 +68,12 @@ def parse_args():
                          "self-attention of a --prefix token prompt on all layers (Sec. 3.1), its own JSON line")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hold", type=float, default=0.0,
+                    help="instead of the benchmark: keep the GPU busy with --hold-what for this many seconds (so that "
+                         "power and clocks can be sampled from outside, e.g. with rocm-smi) and print the rate it ran at")
+    ap.add_argument("--hold-what", choices=["stream", "mfma", "prefix", "step"], default="step",
+                    help="stream: the HBM read calibration kernel; mfma: the matrix-core calibration kernel; prefix: "
+                         "the prefix-pass kernel alone over all layers; step: whole verification steps")
     ap.add_argument("--no-calibrate", action="store_true",
                     help="skip the two calibration kernels (pure HBM read stream, pure bf16 matrix-core loop) whose rates "
                          "are reported as measured_* next to the published peaks")
@@ -202,6 +208,10 @@ def main():
             run_step()
         stream.synchronize()
 
+        if args.hold > 0:
+            return hold(args, sx, torch, stream, run_step, run_prefix, n_layers, layer_bytes,
+                        4.0 * d * T * (Hq // Hkv) * Hkv * L)
+
         # ---- timed region: exactly K steps ----
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -328,6 +338,39 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, n_layers, L, B, topk)
     print(json.dumps(result))
+
+
+def hold(args, sx, torch, stream, run_step, run_prefix, n_layers, layer_bytes, layer_flops):
+    """Loop one kind of work for args.hold seconds and report the rate it sustained."""
+    nbytes = 2 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1) if args.hold_what == "stream" else None
+    flops = [0]
+
+    def mfma():
+        flops[0] = sx.calib_mfma(20000, 32, 512)
+
+    run = {"stream": lambda: sx.calib_stream_read(buf, nbytes), "mfma": mfma, "prefix": run_prefix, "step": run_step}[args.hold_what]
+    run()
+    stream.synchronize()
+    n = 0
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < args.hold:
+        for _ in range(20):
+            run()
+        stream.synchronize()
+        n += 20
+    dt = time.perf_counter() - t0
+    us = dt / n * 1e6
+    out = {"hold": args.hold_what, "seconds": round(dt, 2), "launches": n, "us_per_launch": round(us, 2)}
+    if args.hold_what == "stream":
+        out["GBps"] = round(nbytes / us / 1e3, 1)
+    elif args.hold_what == "mfma":
+        out["TFLOPs"] = round(flops[0] / us / 1e6, 1)
+    else:
+        per = us / n_layers if args.hold_what == "prefix" else us / n_layers
+        out.update({"us_per_layer": round(per, 2), "GBps": round(layer_bytes / per / 1e3, 1),
+                    "TFLOPs": round(layer_flops / per / 1e6, 1)})
+    print(json.dumps(out))
 
 
 def calibrate(sx, torch, stream, event_time_us):

@@ -143,7 +143,11 @@ int resolve(const specext_desc* d, AttnParams* p) {
     const int cus = device_cu_count();
     const int row_groups = (p->M + p->rows_per_group - 1) / p->rows_per_group;
     want = cus / (p->Hkv * row_groups);
-    const int by_len = static_cast<int>((p->L + 255) / 256);
+    // short prefixes: eight key tiles per split, four while that keeps the split count at 16 or
+    // below (measured at 1K - 8K tokens: more splits shorten the prefix kernel by less than they
+    // add to the merge, fewer leave most compute units idle)
+    const int by_256 = static_cast<int>((p->L + 255) / 256), by_128 = static_cast<int>((p->L + 127) / 128);
+    const int by_len = by_256 > (by_128 < 16 ? by_128 : 16) ? by_256 : (by_128 < 16 ? by_128 : 16);
     if (want > by_len) want = by_len;
     if (want < 1) want = 1;
   }
@@ -156,6 +160,11 @@ int resolve(const specext_desc* d, AttnParams* p) {
   // only, and only when all its workgroups fit the device at once (one per compute unit),
   // so that in the normal case nobody waits for a workgroup that has not started.
   const int64_t row_groups = (p->M + p->rows_per_group - 1) / p->rows_per_group;
+  // Workgroups are dealt to the eight XCDs in turn: with the KV head in the fastest grid index and a
+  // multiple of eight heads, all splits of a head run on one XCD, and the head's queries (the only
+  // bytes its workgroups share) are fetched from HBM once instead of once per XCD.  Same run time
+  // (measured), 3.4 MB less HBM traffic per launch at the Llama-3.1-8B shape.
+  p->head_fastest = p->Hkv % 8 == 0 ? 1 : 0;
   p->spin_limit = (d->flags & SPECEXT_FLAG_SHORT_WAIT) ? 0 : kDefaultSpinLimit;
   p->fused_tail = p->use_mfma == 2 && p->S <= 64 && p->L > 0 && p->Hkv * row_groups <= kMaxSyncBlocks &&
                   p->S * p->Hkv * row_groups <= device_cu_count() &&

@@ -59,6 +59,7 @@ struct AttnParams {
   int32_t rows_per_group;         // query rows of one KV head that one workgroup covers
   int32_t part_f16;               // part_o [S][rows][d] holds the unnormalised O as fp16 (1: row-split kernel) or fp32 (0)
   int32_t fused_tail;             // 1: the row-split kernel also runs the tree pass and the merge (no second launch)
+  int32_t head_fastest;           // row-split kernel: grid x = KV head, y = split (else x = split, y = KV head)
   int32_t spin_limit;             // polls of the arrival counter before a workgroup hands its slice to the last arriver
   int32_t in_dtype, out_dtype;
   float scale_log2;

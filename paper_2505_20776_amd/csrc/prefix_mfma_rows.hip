@@ -81,8 +81,8 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const unsigned long long stamp_start = wall_clock64();
 #endif
 
-  const int split = blockIdx.x;
-  const int g = blockIdx.y;
+  const int split = p.head_fastest ? blockIdx.y : blockIdx.x;
+  const int g = p.head_fastest ? blockIdx.x : blockIdx.y;
   const int row0 = blockIdx.z * (WAVES * 32) + wave * 32;
   const int m = row0 + c32;                      // this lane's query row of the KV head
   // a wave whose 32 rows are all padding (fewer rows than the workgroup covers) still loads its
@@ -415,7 +415,7 @@ hipError_t launch_rows(const AttnParams& p, hipStream_t stream) {
     }
   }
   const int rows_per_wg = WAVES * 32;
-  dim3 grid(p.S, p.Hkv, (p.M + rows_per_wg - 1) / rows_per_wg);
+  dim3 grid(p.head_fastest ? p.Hkv : p.S, p.head_fastest ? p.S : p.Hkv, (p.M + rows_per_wg - 1) / rows_per_wg);
   kernel<<<grid, dim3(WAVES * 64), kLdsBytes, stream>>>(p);
   return hipGetLastError();
 }

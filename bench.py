@@ -66,6 +66,9 @@ def parse_args():
     ap.add_argument("--workload", choices=["verify", "prefill"], default="verify",
                     help="verify (default): the verification step the headline metric is quoted on; prefill: causal "
                          "self-attention of a --prefix token prompt on all layers (Sec. 3.1), its own JSON line")
+    ap.add_argument("--merge", choices=["two-launch", "fused"], default="two-launch",
+                    help="tree pass + merge as their own launch (default) or as the tail of the prefix launch "
+                         "(SPECEXT_FLAG_FUSED_MERGE)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hold", type=float, default=0.0,
@@ -129,10 +132,11 @@ def main():
     draft_v = randn(1, Hkv, L, d)
     parent = torch.from_numpy(parent_np).to(dev)
 
+    merge_flag = sx.SPECEXT_FLAG_FUSED_MERGE if args.merge == "fused" else 0
     plain = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
-                                 num_splits=args.num_splits)
+                                 num_splits=args.num_splits, flags=merge_flag)
     last = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
-                                chunk_size=B, want_scores=True, num_splits=args.num_splits)
+                                chunk_size=B, want_scores=True, num_splits=args.num_splits, flags=merge_flag)
     only = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
                                 num_splits=args.num_splits, flags=sx.SPECEXT_FLAG_PREFIX_ONLY)
     outs = [torch.empty((T, Hq, d), dtype=torch.bfloat16, device=dev) for _ in range(n_layers)]
@@ -260,7 +264,7 @@ def main():
     achieved_tf = flops_per_launch / (prefix_us * 1e-6) / 1e12
     step_us = ms_per_step * 1e3
     gather_bytes = 2 * 2 * Hkv * cap * d * 2                   # K and V, read + written
-    default_workload = args.config == "4" and L == 16384 and Hkv == 8 and args.num_splits == 0
+    default_workload = args.config == "4" and L == 16384 and Hkv == 8 and args.num_splits == 0 and args.merge == "two-launch"
     traffic = measured_traffic() if default_workload else None
     result = {
         "metric": "us per verification step (all layers) at 16K prefix" if (args.config == "4" and L == 16384 and Hkv == 8)
@@ -288,6 +292,7 @@ def main():
             "num_splits": sx.num_splits(plain.desc),
             "graph_replay": not args.no_graph,
             "last_layer": args.last_layer,
+            "merge": args.merge,
             "step_hbm_GBps": round(n_layers * bytes_per_launch / (step_us * 1e-6) / 1e9, 1),
             "step_mfma_TFLOPs": round(n_layers * flops_per_launch / (step_us * 1e-6) / 1e12, 1),
             "a1_prefix_us_per_layer": round(prefix_us, 3),

@@ -150,6 +150,13 @@ int specext_workspace_init(void* workspace, size_t workspace_bytes, void* stream
  *   workspace at least specext_workspace_bytes(desc) bytes, 256-byte aligned.
  *
  * Pointers must be 16-byte aligned and strides multiples of 8 elements.
+ * Arithmetic: logits, softmax statistics and the P V sums are fp32 (P and V enter the
+ * matrix cores as bf16).  With bf16 inputs, head_dim 128 and more than 32 rows per KV
+ * head the per-split partial outputs cross memory as fp16 after a per-row power-of-two
+ * rescale (11 bits against the row's largest element, whatever the scale of V); the
+ * rescale exponent travels in the split's softmax reference, so the magnitudes of V
+ * must stay within 2^-100 ... 2^100 and those of two splits of one row within a factor
+ * of about 2^100 of each other, or a split's weight underflows.
  * The first int32 of the workspace is a status word: 0 after a good call,
  * 1 if some parent[i] was >= i or < -1 (that node is then treated as a root),
  * 2 if SPECEXT_FLAG_FUSED_MERGE was set and the workspace was never initialised

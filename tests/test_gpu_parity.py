@@ -244,6 +244,26 @@ def test_value_scale(hx, log2_scale):
     check_attention(wl, res, ref_out, ref_lse, f"V x 2^{log2_scale}")
 
 
+@pytest.mark.parametrize("step_log2", [7, 30, 60])
+def test_value_scale_differs_per_split(hx, step_log2):
+    """The fp16 partials carry a per-row exponent per split: V whose magnitude alternates between neighbouring
+    splits by a factor 2^step (so partials with very different exponents meet in the merge) must still
+    match the oracle on the same values."""
+    import dataclasses
+    wl = config_workload(2, sharp=True, prefix_len=4096)
+    res0 = hx.run_verify(wl, want_scores=False)
+    per = wl.prefix_len // res0["num_splits"]
+    scale = np.where((np.arange(wl.prefix_len) // per) % 2 == 1, np.float32(2.0) ** step_log2, np.float32(1.0)).astype(np.float32)
+    big = dataclasses.replace(wl, v_prefix=wl.v_prefix * scale[None, :, None])
+    ref_out, ref_lse, _ = oracle_all(big)
+    res = hx.run_verify(big, want_scores=False)
+    assert res["status"] == 0 and res["num_splits"] == res0["num_splits"]
+    # the bar is relative to the largest output: bring both sides back to the unscaled magnitude first
+    down = 2.0 ** -step_log2
+    res["out"] = (res["out"].astype(np.float64) * down).astype(np.float32)
+    check_attention(big, res, ref_out * down, ref_lse, f"V x 2^{step_log2} on odd splits")
+
+
 # --------------------------------------------------------------------------
 # SelectChunks on its own: bit-exact against the oracle on the same fp32 values
 # --------------------------------------------------------------------------

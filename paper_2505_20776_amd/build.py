@@ -28,15 +28,22 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found (set HIPCC or install ROCm under /opt/rocm)")
 
 
-def build_library(verbose: bool = True) -> str:
-    """Compile every HIP source for gfx950 and link libspecext.so next to this file."""
-    obj_dir = os.path.join(PKG_DIR, "_build")
+STAMPS_LIB_PATH = os.path.join(PKG_DIR, "libspecext_stamps.so")
+
+
+def build_library(verbose: bool = True, stamps: bool = False) -> str:
+    """Compile every HIP source for gfx950 and link libspecext.so next to this file.
+    stamps=True builds the profiling variant libspecext_stamps.so instead (-DSPECEXT_TAIL_STAMPS: the row-split
+    prefix kernel and the fused merge tail leave wall-clock stamps of their phases in the workspace; see
+    paper_2505_20776_amd/phase_stamps.py)."""
+    obj_dir = os.path.join(PKG_DIR, "_build_stamps" if stamps else "_build")
     os.makedirs(obj_dir, exist_ok=True)
     common = [
         hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
-    ]
+    ] + (["-DSPECEXT_TAIL_STAMPS"] if stamps else [])
+    lib_path = STAMPS_LIB_PATH if stamps else LIB_PATH
     procs = []
     objs = []
     for src in SOURCES:
@@ -55,11 +62,11 @@ def build_library(verbose: bool = True) -> str:
             sys.stderr.write(f"[specext build] {src}:\n{out}\n")
     if failed:
         raise RuntimeError("hipcc failed")
-    tmp = LIB_PATH + ".tmp"
+    tmp = lib_path + ".tmp"
     subprocess.run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs, check=True)
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    os.replace(tmp, lib_path)
+    return lib_path
 
 
 if __name__ == "__main__":
-    print(build_library())
+    print(build_library(stamps="--stamps" in sys.argv[1:]))

@@ -330,6 +330,17 @@ int specext_workspace_init(void* workspace, size_t workspace_bytes, void* stream
   return hipGetLastError() == hipSuccess ? SPECEXT_OK : SPECEXT_ERR_LAUNCH_FAILED;
 }
 
+#ifdef SPECEXT_TAIL_STAMPS
+// Profiling builds only (not in the public header): byte offset, inside the workspace, of the phase stamps the
+// row-split prefix kernel leaves per workgroup - eight 64-bit wall-clock values (100 MHz) for workgroup
+// (row group z, KV head g, split s) at index ((z * Hkv + g) * S + s) * 8.  0 if the descriptor takes another kernel.
+size_t specext_debug_stamps_offset(const specext_desc* desc) {
+  AttnParams p;
+  if (resolve(desc, &p) != SPECEXT_OK || p.use_mfma != 2) return 0;
+  return layout_of(p).part_o_off + static_cast<size_t>(p.S) * p.Hq * p.T * p.d * 2;
+}
+#endif
+
 int specext_num_splits(const specext_desc* desc) {
   AttnParams p;
   const int rc = resolve(desc, &p);

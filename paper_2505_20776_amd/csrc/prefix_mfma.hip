@@ -22,19 +22,10 @@
 //   contraction order and V is fetched in that same order, so P never moves
 //   between lanes.
 // Row max / row sum therefore live in one lane pair (lane, lane^32).
-#include "common.h"
+#include "mfma_util.h"
 
 namespace specext {
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float floatx2;
-typedef __attribute__((ext_vector_type(4))) float floatx4;
-typedef __attribute__((ext_vector_type(16))) float floatx16;
-typedef __attribute__((ext_vector_type(4))) short shortx4;
-typedef __attribute__((ext_vector_type(8))) short shortx8;
-typedef __attribute__((ext_vector_type(4))) uint32_t uintx4;
 
 constexpr int kWaves = 4;
 constexpr int kTile = 32;                         // keys per wave tile
@@ -47,27 +38,6 @@ constexpr int kStageBytes = (kKSlots + kVSlots) * kTileBytes;   // 40 KB per wav
 constexpr int kMergeFloatsPerWave = 4 * 2 * 16 * 64;   // O^T dump at RB = 2
 constexpr int kMergeBytes = kWaves * kMergeFloatsPerWave * 4 + kWaves * 2 * 2 * 32 * 4;
 constexpr int kLdsBytes = kMergeBytes > kWaves * kStageBytes ? kMergeBytes : kWaves * kStageBytes;
-// The running reference of a row only moves when a tile's max exceeds it by more
-// than this many powers of two, so exp2(s - ref) stays below 2^kLazyLog2.
-constexpr float kLazyLog2 = 10.f;
-
-typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
-typedef __attribute__((address_space(3))) void lds_void;
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-__device__ __forceinline__ bf16x8 pack8(const floatx16& v, int first) {
-  bf16x8 out;
-#pragma unroll
-  for (int e = 0; e < 8; e += 2) {
-    floatx2 f = {v[first + e], v[first + e + 1]};
-    bf16x2 b = __builtin_convertvector(f, bf16x2);
-    out[e] = b[0];
-    out[e + 1] = b[1];
-  }
-  return out;
-}
-
 // Wait until at most 8 * groups vector-memory operations are outstanding.
 __device__ __forceinline__ void wait_vm_groups(int groups) {
   switch (groups) {

@@ -78,7 +78,11 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const int c32 = lane & 31;
   const int hf = lane >> 5;
 #ifdef SPECEXT_TAIL_STAMPS
+  // profiling build: wall-clock stamps (100 MHz) of this workgroup's phases, left in the unused upper half
+  // of the partial-output region (sized for fp32, holding fp16): 0 start, 1 first tile ready, 2 last tile
+  // done, 3 partial stores issued (the fused tail, when it runs, overwrites 1.. with its own phases)
   const unsigned long long stamp_start = wall_clock64();
+  unsigned long long stamp_first = 0, stamp_loop = 0;
 #endif
 
   const int split = p.head_fastest ? blockIdx.y : blockIdx.x;
@@ -320,6 +324,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
           wait_vmcnt_even(younger_than_stage(s));
         }
         lds_barrier();
+#ifdef SPECEXT_TAIL_STAMPS
+        if (s == 0) stamp_first = wall_clock64();
+#endif
         if (s + kStages - 1 < n_stages) issue_stage(ic<(u + kStages - 1) % kStages>{}, s + kStages - 1);
         static_for<0, kStageTiles>([&](auto i_c) {
           constexpr int i = decltype(i_c)::value;
@@ -330,6 +337,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     });
   }
 
+#ifdef SPECEXT_TAIL_STAMPS
+  stamp_loop = wall_clock64();
+#endif
   // ---- partial results of this split: the triple (reference, row sum, unnormalised O)
   // is rescaled by the power of two that brings the row's largest |O| just below 1
   // (O * 2^-e, sum * 2^-e, reference + e describe the same partial), and O goes out as
@@ -386,14 +396,19 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     if (p.fused_tail) store_device_scope_8(dst, v);
     else __builtin_nontemporal_store(v, reinterpret_cast<floatx2*>(dst));
   }
+#ifdef SPECEXT_TAIL_STAMPS
+  if (threadIdx.x == 0) {
+    unsigned long long* st = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(p.part_o) +
+                                                                   static_cast<size_t>(p.S) * p.Hq * p.T * kD * 2) +
+                             ((blockIdx.z * p.Hkv + g) * p.S + split) * 8;
+    st[0] = stamp_start;
+    st[1] = stamp_first;
+    st[2] = stamp_loop;
+    st[3] = wall_clock64();
+  }
+#endif
   // tree pass and merge in the same launch: this workgroup merges its slice of the head's rows
   if (p.fused_tail) {
-#ifdef SPECEXT_TAIL_STAMPS
-    if (threadIdx.x == 0)
-      (reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(p.part_o) +
-                                             static_cast<size_t>(p.S) * p.Hq * p.T * kD * 2) +
-       ((blockIdx.z * p.Hkv + g) * p.S + split) * 8)[0] = stamp_start;
-#endif
     tree_merge_tail<WAVES * 64>(p, lds, tail_priv, split, g, blockIdx.z, WAVES * 32, epoch, cookie_ok);
   }
 }

@@ -1,0 +1,78 @@
+"""Where the time of the row-split prefix kernel goes, from wall-clock stamps the kernel leaves per workgroup.
+
+Needs the profiling build of the library and one MI355X:
+
+    python -m paper_2505_20776_amd.build --stamps
+    SPECEXT_LIBRARY=paper_2505_20776_amd/libspecext_stamps.so python -m paper_2505_20776_amd.phase_stamps [--prefix 16384] [--merge fused]
+
+Runs the Llama-3.1-8B layer shape of the benchmark (60-node tree, 8 layers of distinct K/V so that every launch
+streams from HBM), reads the stamps of the last launch of each pass and prints, in microseconds after the first
+workgroup's start and averaged over the passes: workgroup start, first key tile ready, last key tile done, partial
+stores issued (and, with --merge fused, the phases of the merge tail), the spread between XCDs and the time per
+key tile.  The stamps come from the GPU's 100 MHz wall clock: 10 ns resolution.
+"""
+import argparse
+import ctypes
+
+import numpy as np
+import torch
+
+import paper_2505_20776_amd as sx
+from paper_2505_20776_amd import harness
+from workloads import config_tree
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--prefix", type=int, default=16384)
+    ap.add_argument("--merge", choices=["two-launch", "fused"], default="two-launch")
+    ap.add_argument("--passes", type=int, default=6)
+    a = ap.parse_args()
+    lib = sx.load_library()
+    if not hasattr(lib, "specext_debug_stamps_offset"):
+        raise SystemExit("this library was built without -DSPECEXT_TAIL_STAMPS: see the module's docstring")
+    lib.specext_debug_stamps_offset.restype = ctypes.c_size_t
+    lib.specext_debug_stamps_offset.argtypes = [ctypes.POINTER(sx.specext_desc)]
+    dev, Hq, Hkv, d, L, n_layers = "cuda", 32, 8, 128, a.prefix, 8
+    parent_np = config_tree(4)
+    T = len(parent_np)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    rn = lambda *s: (torch.randn(*s, generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)
+    q = [rn(T, Hq, d) for _ in range(n_layers)]
+    kp, vp = [rn(Hkv, L, d) for _ in range(n_layers)], [rn(Hkv, L, d) for _ in range(n_layers)]
+    kt, vt = [rn(Hkv, T, d) for _ in range(n_layers)], [rn(Hkv, T, d) for _ in range(n_layers)]
+    parent = torch.from_numpy(parent_np).to(dev)
+    fused = a.merge == "fused"
+    buf = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
+                               flags=sx.SPECEXT_FLAG_FUSED_MERGE if fused else 0)
+    S = sx.num_splits(buf.desc)
+    off = int(lib.specext_debug_stamps_offset(ctypes.byref(buf.desc)))
+    assert off > 0
+    n_st = 7 if fused else 4
+    acc = []
+    for it in range(a.passes + 2):
+        for l in range(n_layers):
+            sx.verify_attn(buf.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, buf.out, buf.lse, buf.workspace)
+        torch.cuda.synchronize()
+        st = buf.workspace[off:off + Hkv * S * 64].view(torch.int64).cpu().numpy().reshape(Hkv, S, 8).astype(np.float64)
+        if it >= 2:
+            acc.append((st[:, :, :n_st] - st[:, :, 0].min()) / 100.0)
+    us = np.mean(acc, axis=0)
+    names = (["workgroup start", "last key tile done (tail entry)", "own partial acknowledged, flag stored", "tree part done",
+              "all flags seen", "own slice merged and written", "done"] if fused else
+             ["workgroup start", "first key tile ready", "last key tile done", "partial stores issued"])
+    tiles = -(-(-(-L // S)) // 32)
+    print(f"prefix {L}, {S} splits x {Hkv} KV heads = {S * Hkv} workgroups, {tiles} key tiles each, merge: {a.merge}")
+    print(f"{'phase':42s} {'min':>8s} {'median':>8s} {'max':>8s}   (us after the first workgroup's start)")
+    for i, n in enumerate(names):
+        v = us[:, :, i]
+        print(f"{n:42s} {v.min():8.2f} {np.median(v):8.2f} {v.max():8.2f}")
+    last = 1 if fused else 2
+    print("last key tile done, mean per KV head (one head per XCD):", " ".join(f"{us[h, :, last].mean():.2f}" for h in range(Hkv)))
+    if not fused:
+        print(f"key-tile loop: {np.median(us[:, :, 2] - us[:, :, 1]) / tiles:.3f} us per tile (median workgroup)")
+
+
+if __name__ == "__main__":
+    main()

@@ -47,13 +47,16 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", choices=["2", "3", "4", "5wide", "5chain", "draft"], default="4",
+    ap.add_argument("--config", choices=["2", "3", "4", "5wide", "5chain", "draft", "draft68m"], default="4",
                     help="numbered workload: 4 (default) = 32 layers at a 16K prefix, the headline metric; 2 / 3 / 5 = "
                          "the single-layer shapes (2K, 8K, 32K-37 with a 128-node wide tree or a 16-node chain), run "
                          "over enough distinct K/V copies (>= 300 MB) that every launch streams cold (a second figure, "
                          "labelled hot, comes from one copy that stays in the caches); draft = the draft model's side "
                          "(Sec. 3.2.1): one EAGLE-style layer of the same shape over a compacted working cache of "
-                         "2048 tokens")
+                         "2048 tokens; draft68m = a Vicuna-68M-shaped draft layer (12 heads of 64, no grouping) over "
+                         "a working cache of 1024 tokens")
+    ap.add_argument("--valu-prefix", action="store_true",
+                    help="prefix pass on the vector ALUs (SPECEXT_FLAG_VALU_PREFIX) instead of the matrix cores")
     ap.add_argument("--kv-heads", type=int, default=8,
                     help="KV heads (8 = Llama-3.1-8B's grouped queries; 32 = multi-head attention as in the "
                          "Vicuna-7B / LongChat-7B targets of the paper)")
@@ -104,11 +107,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    Hq, Hkv, d = 32, args.kv_heads, 128
+    Hq, Hkv, d = (12, 12, 64) if args.config == "draft68m" else (32, args.kv_heads, 128)
     L, B, topk, parent_np = {"2": (2048, 32, 32, config_tree(2)), "3": (8192, 32, 32, config_tree(3)),
                              "4": (16384, 32, 32, config_tree(4)), "5wide": (32768 - 37, 64, 16, config_tree(5, "wide")),
                              "5chain": (32768 - 37, 64, 16, config_tree(5, "chain")),
-                             "draft": (2048, 32, 32, config_tree(2))}[args.config]
+                             "draft": (2048, 32, 32, config_tree(2)), "draft68m": (1024, 32, 32, config_tree(2))}[args.config]
     L = args.prefix or L
     T = len(parent_np)
     layer_bytes = 2 * Hkv * L * d * 2
@@ -132,13 +135,15 @@ def main():
     draft_v = randn(1, Hkv, L, d)
     parent = torch.from_numpy(parent_np).to(dev)
 
-    merge_flag = sx.SPECEXT_FLAG_FUSED_MERGE if args.merge == "fused" else 0
+    merge_flag = (sx.SPECEXT_FLAG_FUSED_MERGE if args.merge == "fused" else 0) | \
+                 (sx.SPECEXT_FLAG_VALU_PREFIX if args.valu_prefix else 0)
     plain = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
                                  num_splits=args.num_splits, flags=merge_flag)
     last = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
                                 chunk_size=B, want_scores=True, num_splits=args.num_splits, flags=merge_flag)
     only = harness.make_buffers(dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, prefix_len=L, n_tree=T,
-                                num_splits=args.num_splits, flags=sx.SPECEXT_FLAG_PREFIX_ONLY)
+                                num_splits=args.num_splits, flags=sx.SPECEXT_FLAG_PREFIX_ONLY |
+                                (sx.SPECEXT_FLAG_VALU_PREFIX if args.valu_prefix else 0))
     outs = [torch.empty((T, Hq, d), dtype=torch.bfloat16, device=dev) for _ in range(n_layers)]
     scores = torch.empty((n_chunks,), dtype=torch.float32, device=dev)
     idx = torch.empty((topk,), dtype=torch.int32, device=dev)
@@ -281,8 +286,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"config {args.config}: {n_layers} layers x (Hq=32, Hkv={Hkv}, d=128) bf16, prefix {L}, {T}-node tree, "
-                        f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x{Hkv}x{cap}x128"
+            "workload": f"config {args.config}: {n_layers} layers x (Hq={Hq}, Hkv={Hkv}, d={d}) bf16, prefix {L}, {T}-node tree, "
+                        f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x{Hkv}x{cap}x{d}"
                         + (" (every layer its own K/V copy: cold)" if single else ""),
             "arithmetic": "bf16 inputs, fp32 accumulation on the matrix cores; split partials cross HBM as fp16 "
                           "after a per-row power-of-two rescale",
@@ -303,8 +308,9 @@ def main():
             "gather_copy_frac": round(gather_bytes / (a6_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
         },
         "roofline": {
-            "kernel": ("prefix_rows_kernel" if T * (Hq // Hkv) > 32 else "prefix_mfma_kernel") +
-                      " (split-K prefix pass on the matrix cores, one layer per launch)",
+            "kernel": ("prefix_generic_kernel (split-K prefix pass on the vector ALUs" if args.valu_prefix else
+                       ("prefix_rows_kernel" if (T * (Hq // Hkv) > 32 or d == 64) else "prefix_mfma_kernel") +
+                       " (split-K prefix pass on the matrix cores") + ", one layer per launch)",
             "bound": "hbm",
             "achieved": round(achieved_gbs, 1),
             "peak": HBM_PEAK_GBS,
@@ -473,14 +479,19 @@ def cpu_baseline(args, n_layers, L, B, topk):
     import numpy as np
 
     import oracle as orc
-    from workloads import config_workload
+    from workloads import config_tree, config_workload
 
     sample_layers = max(1, min(args.cpu_layers, n_layers))
     t_attn = 0.0
     wl = None
     for l in range(sample_layers):
-        cfg = 2 if args.config == "draft" else int(args.config[0])
-        wl = config_workload(cfg, item=l, prefix_len=L, variant="" if args.config == "draft" else args.config[1:])
+        if args.config == "draft68m":
+            from workloads import make_workload
+            wl = make_workload("draft68m", seed=6800 + l, dtype="bf16", n_q_heads=12, n_kv_heads=12, head_dim=64,
+                               prefix_len=L, parent=config_tree(2), chunk_size=B, top_k=topk, n_needles=0)
+        else:
+            cfg = 2 if args.config == "draft" else int(args.config[0])
+            wl = config_workload(cfg, item=l, prefix_len=L, variant="" if args.config == "draft" else args.config[1:])
         t0 = time.perf_counter()
         orc.verify_attention(wl.q, wl.k_prefix, wl.v_prefix, wl.k_tree, wl.v_tree, wl.parent)
         t_attn += time.perf_counter() - t0

@@ -96,8 +96,9 @@ typedef struct specext_desc {
   int32_t head_dim;       /* d: 64 or 128 */
   int32_t prefix_len;     /* 0 <= L <= 2^30 cached positions */
   int32_t n_tree;         /* T in [1, SPECEXT_MAX_TREE] */
-  int32_t chunk_size;     /* 0 < B <= 2^24; only read when want_scores != 0.  The bf16 fast path
-                             needs B to be a multiple of 32; other values take the generic kernel. */
+  int32_t chunk_size;     /* 0 < B <= 2^24; only read when want_scores != 0.  The bf16 matrix-core
+                             kernels need B to be a multiple of 32 (and, for head_dim 64, kp_stride_l = 64);
+                             other values take the vector-ALU kernel. */
   int32_t want_scores;    /* != 0: also leave per-chunk partial sums in the workspace */
   int32_t num_splits;     /* pieces the prefix is cut into; 0 = choose automatically */
   float softmax_scale;    /* 0 = 1/sqrt(d) */

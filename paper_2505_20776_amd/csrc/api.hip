@@ -108,11 +108,18 @@ int resolve(const specext_desc* d, AttnParams* p) {
   // (a workgroup owns 128 or 256 rows, so each K/V byte enters one compute unit only;
   // measured faster from 33 rows on, also when most of a workgroup's rows are padding).
   // Their address arithmetic inside a tile and inside Q is 32-bit, hence the stride limits.
-  const bool mfma_ok = p->in_dtype == SPECEXT_BF16 && p->d == 128 && p->L >= 32 &&
-                       (!p->want_scores || p->B % 32 == 0) && !(d->flags & SPECEXT_FLAG_VALU_PREFIX) &&
-                       p->kp_sl <= (1 << 24) &&
-                       (p->T - 1) * p->q_st + (p->Hq - 1) * p->q_sh + p->d < (int64_t{1} << 30);
-  if (!mfma_ok) {
+  const bool mfma_common = p->in_dtype == SPECEXT_BF16 && (!p->want_scores || p->B % 32 == 0) &&
+                           !(d->flags & SPECEXT_FLAG_VALU_PREFIX) && p->kp_sl <= (1 << 24) &&
+                           (p->T - 1) * p->q_st + (p->Hq - 1) * p->q_sh + p->d < (int64_t{1} << 30);
+  const bool mfma_ok = mfma_common && p->d == 128 && p->L >= 32;
+  // head_dim 64 (small draft models): the row-split kernel with two keys per LDS row, which needs the
+  // keys of a head contiguous in memory and at least one 64-key tile
+  const bool mfma64_ok = mfma_common && p->d == 64 && p->kp_sl == 64 && p->L >= 64;
+  if (mfma64_ok) {
+    p->use_mfma = 2;
+    p->rows_per_group = p->M > 128 ? 256 : 128;
+    p->part_f16 = 0;
+  } else if (!mfma_ok) {
     p->use_mfma = 0;
     p->rows_per_group = 64;
   } else if (p->M <= 32) {
@@ -166,7 +173,7 @@ int resolve(const specext_desc* d, AttnParams* p) {
   // (measured), 3.4 MB less HBM traffic per launch at the Llama-3.1-8B shape.
   p->head_fastest = p->Hkv % 8 == 0 ? 1 : 0;
   p->spin_limit = (d->flags & SPECEXT_FLAG_SHORT_WAIT) ? 0 : kDefaultSpinLimit;
-  p->fused_tail = p->use_mfma == 2 && p->S <= 64 && p->L > 0 && p->Hkv * row_groups <= kMaxSyncBlocks &&
+  p->fused_tail = p->use_mfma == 2 && p->part_f16 && p->S <= 64 && p->L > 0 && p->Hkv * row_groups <= kMaxSyncBlocks &&
                   p->S * p->Hkv * row_groups <= device_cu_count() &&
                   (d->flags & SPECEXT_FLAG_FUSED_MERGE) && !(d->flags & SPECEXT_FLAG_PREFIX_ONLY);
   return SPECEXT_OK;
@@ -336,7 +343,7 @@ int specext_workspace_init(void* workspace, size_t workspace_bytes, void* stream
 // (row group z, KV head g, split s) at index ((z * Hkv + g) * S + s) * 8.  0 if the descriptor takes another kernel.
 size_t specext_debug_stamps_offset(const specext_desc* desc) {
   AttnParams p;
-  if (resolve(desc, &p) != SPECEXT_OK || p.use_mfma != 2) return 0;
+  if (resolve(desc, &p) != SPECEXT_OK || p.use_mfma != 2 || !p.part_f16) return 0;
   return layout_of(p).part_o_off + static_cast<size_t>(p.S) * p.Hq * p.T * p.d * 2;
 }
 #endif

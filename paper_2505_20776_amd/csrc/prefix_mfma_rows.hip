@@ -68,10 +68,20 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <int WAVES, bool SCORES>
+// KPR = keys per 256-byte LDS row: 1 for head_dim 128.  For head_dim 64 (KPR = 2, keys
+// contiguous in memory) two consecutive keys share a row and the whole tile machinery -
+// loads, swizzles, operand reads - is the same; a tile is then 64 keys, the logits of the
+// even and of the odd keys of the rows come from the first and the second half of the
+// K fragments against the same four query fragments, and the even / odd probabilities
+// meet V^T's first / second pair of 32-column blocks in the same two output blocks.
+template <int WAVES, bool SCORES, int KPR>
 __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   constexpr int kLoadsPerWave = 8 / WAVES;       // 1 KB blocks of a tile that one wave fills (per K or V)
+  constexpr int kKeysPerTile = kTile * KPR;
+  constexpr int kQSteps = 8 / KPR;               // 16-wide contraction steps of one query row
+  constexpr int kOBlocks = 4 / KPR;              // 32-column blocks of the output
+  constexpr int kHeadDim = kD / KPR;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -95,9 +105,10 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
 
   const int key_lo = split * p.keys_per_split;
   const int key_hi = min(p.L, key_lo + p.keys_per_split);
-  const int n = (key_hi - key_lo + kTile - 1) / kTile;          // tiles of this split (>= 1)
+  const int n = (key_hi - key_lo + kKeysPerTile - 1) / kKeysPerTile;          // tiles of this split (>= 1)
 
-  const int64_t row_bytes = p.kp_sl * 2;
+  const int64_t key_bytes = p.kp_sl * 2;
+  const int64_t row_bytes = key_bytes * KPR;     // from one LDS row's first key to the next one's (KPR = 2: kp_sl = 64)
   const unsigned char* kbase = static_cast<const unsigned char*>(p.kp) + static_cast<int64_t>(g) * p.kp_sh * 2;
   const unsigned char* vbase = static_cast<const unsigned char*>(p.vp) + static_cast<int64_t>(g) * p.kp_sh * 2;
 
@@ -118,15 +129,15 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const unsigned v_voff = static_cast<unsigned>(ld_row * row_bytes) + ((ld_slot ^ (ld_row << 2)) << 4);
 
   // First key of the 32 rows tile t loads.  The last tile of a ragged split is shifted
-  // back so that it ends exactly at key_hi (no load ever leaves the prefix); its rows
+  // back so that it ends exactly at key_hi (no load ever leaves the prefix); its keys
   // below the tile's own first key belong to the tile before and are masked.
-  auto tile_key0 = [&](int t) { return key_lo + t * kTile; };
-  auto tile_first_row = [&](int t) { return min(tile_key0(t), key_hi - kTile); };
+  auto tile_key0 = [&](int t) { return key_lo + t * kKeysPerTile; };
+  auto tile_first_row = [&](int t) { return min(tile_key0(t), key_hi - kKeysPerTile); };
   // this wave's share of K(t), then of V(t), into ring slot SLOT (a compile-time constant,
   // so that every LDS address below is a loop-invariant register plus an immediate)
   auto issue_tile = [&](auto slot_c, int t) {
     constexpr unsigned slot = decltype(slot_c)::value * kTileBytes;
-    const int64_t off = static_cast<int64_t>(tile_first_row(t)) * row_bytes;
+    const int64_t off = static_cast<int64_t>(tile_first_row(t)) * key_bytes;
 #pragma unroll
     for (int u = 0; u < kLoadsPerWave; ++u) {
       const int blk = kLoadsPerWave * wave + u;
@@ -173,7 +184,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       const int mq = min(row0 + r, p.M - 1);               // padding rows repeat the last real row (never stored)
       const int tq = static_cast<int>((static_cast<float>(mq) + 0.5f) * inv_g);   // mq / G, exact for mq < 2^20
       const int hq = g * p.G + (mq - tq * p.G);
-      const unsigned voff = static_cast<unsigned>((tq * p.q_st + hq * p.q_sh) * 2) + ((ld_slot ^ (r & 15)) << 4);
+      // (a 64-wide query row has eight 16-byte chunks: the lanes of the other eight slots re-read them, unused)
+      const unsigned voff = static_cast<unsigned>((tq * p.q_st + hq * p.q_sh) * 2) +
+                            (((ld_slot ^ (r & 15)) & (KPR == 2 ? 7 : 15)) << 4);
       load_to_lds_16(priv_lds + u * 1024, voff, qbase);
     }
   }
@@ -218,11 +231,11 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
 
   // queries: B operand of S^T (lane = row c32, 8 consecutive d per k-step), read from
   // the private area once the first wait below has passed
-  bf16x8 qf[8];
+  bf16x8 qf[kQSteps];
   unsigned char* priv = lds + kRingBytes + wave * kPrivBytes;
-  floatx16 acc_o[4];
+  floatx16 acc_o[kOBlocks];
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
+  for (int db = 0; db < kOBlocks; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
   float ref = -INFINITY;       // reference logit (raw units) the exponentials are taken against
@@ -240,11 +253,15 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   // lazily), O^T += V^T P^T.  SLOT is the tile's ring slot.
   auto tile = [&](auto slot_c, int j) {
     constexpr int slot = decltype(slot_c)::value * kTileBytes;
-    floatx16 s = zero16;
+    floatx16 s[KPR];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const uintx4 kw = *reinterpret_cast<const uintx4*>(lds + k_rd[ks] + slot);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[ks], s, 0, 0, 0);
+    for (int kp = 0; kp < KPR; ++kp) {
+      s[kp] = zero16;
+#pragma unroll
+      for (int ks = 0; ks < kQSteps; ++ks) {
+        const uintx4 kw = *reinterpret_cast<const uintx4*>(lds + k_rd[ks + kp * kQSteps] + slot);
+        s[kp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[ks], s[kp], 0, 0, 0);
+      }
     }
     bf16x8 vf[4][2];             // the tile's V^T fragments
 #pragma unroll
@@ -259,17 +276,22 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       }
     }
     const int key0 = tile_key0(j);
-    const int first_row = tile_first_row(j);
-    if (first_row < key0) {          // rows of a shifted last tile that belong to the tile before
-      const int thr = key0 - first_row - 4 * hf;     // register r holds key first_row + 4*hf + 8*(r/4) + r%4
+    const int first_key = tile_first_row(j);
+    // register r of s[kp] holds key first_key + KPR * (4*hf + 8*(r/4) + r%4) + kp
+    const int skip = key0 - first_key - KPR * 4 * hf;     // > 0 only in a shifted last tile: keys of the tile before
+    if (first_key < key0) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (8 * (r >> 2) + (r & 3) < thr) s[r] = -INFINITY;
-      }
+      for (int kp = 0; kp < KPR; ++kp)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (KPR * (8 * (r >> 2) + (r & 3)) + kp < skip) s[kp][r] = -INFINITY;
+        }
     }
-    float mx = fmaxf(s[0], s[1]);
+    float mx = fmaxf(s[0][0], s[0][1]);
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[r], s[r + 1]));
+    for (int kp = 0; kp < KPR; ++kp)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[kp][r], s[kp][r + 1]));
     if (__any(mx > ref + lazy_raw)) {     // some row of this wave outgrew its reference: move every reference up
       mx = halves_max(mx);
       const float new_ref = fmaxf(ref, mx);
@@ -277,30 +299,59 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       ref = new_ref;
       run_sum *= alpha;
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+      for (int db = 0; db < kOBlocks; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
     }
     const float mc = ref * c;
-    float part = 0.f;
+    // exponentials; their sums per 32-key score block: a tile is one block (KPR = 1) or two
+    // (KPR = 2: the keys of LDS rows 0..15, registers 0..7, then those of rows 16..31)
+    float part[KPR];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s[r] = fast_exp2(fmaf(s[r], c, -mc));
-      part += s[r];
+    for (int b = 0; b < KPR; ++b) part[b] = 0.f;
+    if (KPR == 2 && SCORES && first_key < key0) {
+      // shifted last tile: its rows no longer line up with the score blocks; sort every key by its position
+#pragma unroll
+      for (int kp = 0; kp < KPR; ++kp)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          s[kp][r] = fast_exp2(fmaf(s[kp][r], c, -mc));
+          if (KPR * (8 * (r >> 2) + (r & 3)) + kp - skip >= kTile) part[KPR - 1] += s[kp][r];
+          else part[0] += s[kp][r];
+        }
+    } else {
+#pragma unroll
+      for (int kp = 0; kp < KPR; ++kp)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          s[kp][r] = fast_exp2(fmaf(s[kp][r], c, -mc));
+          part[KPR == 2 ? (r >> 3) : 0] += s[kp][r];
+        }
     }
-    run_sum += part;
+#pragma unroll
+    for (int b = 0; b < KPR; ++b) run_sum += part[b];
     if (SCORES) {
-      const float tot = halves_sum(part);
-      if (hf == 0 && m < p.M) {
-        *reinterpret_cast<floatx2*>(score_base + j * score_step) = floatx2{tot, mc};
+#pragma unroll
+      for (int b = 0; b < KPR; ++b) {
+        const float tot = halves_sum(part[b]);
+        if (hf == 0 && m < p.M && key0 + b * kTile < key_hi) {
+          *reinterpret_cast<floatx2*>(score_base + (j * KPR + b) * score_step) = floatx2{tot, mc};
+        }
       }
     }
-    const bf16x8 pf0 = pack8(s, 0);
-    const bf16x8 pf1 = pack8(s, 8);
+    bf16x8 pf[KPR][2];
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][0], pf0, acc_o[db], 0, 0, 0);
-      acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][1], pf1, acc_o[db], 0, 0, 0);
+    for (int kp = 0; kp < KPR; ++kp) {
+      pf[kp][0] = pack8(s[kp], 0);
+      pf[kp][1] = pack8(s[kp], 8);
+    }
+#pragma unroll
+    for (int db = 0; db < kOBlocks; ++db) {
+#pragma unroll
+      for (int kp = 0; kp < KPR; ++kp) {
+        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db + kp * kOBlocks][0], pf[kp][0], acc_o[db], 0, 0, 0);
+        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db + kp * kOBlocks][1], pf[kp][1], acc_o[db], 0, 0, 0);
+      }
     }
   };
 
@@ -316,7 +367,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
         if (s == 0) {
           wait_vmcnt_even(younger_than_stage(0));        // also covers the wave's own queries
 #pragma unroll
-          for (int ks = 0; ks < 8; ++ks)
+          for (int ks = 0; ks < kQSteps; ++ks)
             qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(priv + k_rd[ks]));
         } else if ((s + kStages - 1) * kStageTiles <= n) {
           asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kLoadsPerTile * kStageTiles * (kStages - 2)) : "memory");
@@ -340,13 +391,29 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
 #ifdef SPECEXT_TAIL_STAMPS
   stamp_loop = wall_clock64();
 #endif
+  const float l_tot = halves_sum(run_sum);
+  const int64_t slot0 = static_cast<int64_t>(split) * p.Hq * p.T + g * p.M + row0;     // slot of the wave's first row
+  if constexpr (KPR == 2) {
+    // ---- head_dim 64: the partial goes out as it is, (reference, row sum) and the unnormalised
+    // O in fp32 (what the merge kernel reads for this head size); a lane owns one row and
+    // holds four consecutive columns per register quad
+    if (m < p.M) {
+      float* dst = p.part_o + (slot0 + c32) * kHeadDim;
+#pragma unroll
+      for (int db = 0; db < kOBlocks; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          __builtin_nontemporal_store(floatx4{acc_o[db][4 * r4], acc_o[db][4 * r4 + 1], acc_o[db][4 * r4 + 2], acc_o[db][4 * r4 + 3]},
+                                      reinterpret_cast<floatx4*>(dst + 32 * db + 8 * r4 + 4 * hf));
+      if (hf == 0) __builtin_nontemporal_store(floatx2{ref * c, l_tot}, reinterpret_cast<floatx2*>(p.part_ml + (slot0 + c32) * 2));
+    }
+  } else {
   // ---- partial results of this split: the triple (reference, row sum, unnormalised O)
   // is rescaled by the power of two that brings the row's largest |O| just below 1
   // (O * 2^-e, sum * 2^-e, reference + e describe the same partial), and O goes out as
   // fp16: every row keeps 11 bits against its own largest element whatever the scale of
   // V.  O^T sits in registers with a lane owning one row; it goes through the wave's
   // private LDS area so that the global stores are whole 256-byte rows.
-  const float l_tot = halves_sum(run_sum);
   float row_max = 0.f;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
@@ -359,7 +426,6 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     const floatx2 f = {x * row_scale, y * row_scale};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, halfx2));
   };
-  const int64_t slot0 = static_cast<int64_t>(split) * p.Hq * p.T + g * p.M + row0;     // slot of the wave's first row
   const int rows_here = min(32, p.M - row0);       // <= 0 for a wave of padding rows only
 #pragma unroll
   for (int db = 0; db < 4; ++db) {
@@ -396,8 +462,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     if (p.fused_tail) store_device_scope_8(dst, v);
     else __builtin_nontemporal_store(v, reinterpret_cast<floatx2*>(dst));
   }
+  }
 #ifdef SPECEXT_TAIL_STAMPS
-  if (threadIdx.x == 0) {
+  if (KPR == 1 && threadIdx.x == 0) {
     unsigned long long* st = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(p.part_o) +
                                                                    static_cast<size_t>(p.S) * p.Hq * p.T * kD * 2) +
                              ((blockIdx.z * p.Hkv + g) * p.S + split) * 8;
@@ -408,14 +475,14 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   }
 #endif
   // tree pass and merge in the same launch: this workgroup merges its slice of the head's rows
-  if (p.fused_tail) {
-    tree_merge_tail<WAVES * 64>(p, lds, tail_priv, split, g, blockIdx.z, WAVES * 32, epoch, cookie_ok);
+  if constexpr (KPR == 1) {
+    if (p.fused_tail) tree_merge_tail<WAVES * 64>(p, lds, tail_priv, split, g, blockIdx.z, WAVES * 32, epoch, cookie_ok);
   }
 }
 
-template <int WAVES, bool SCORES>
+template <int WAVES, bool SCORES, int KPR>
 hipError_t launch_rows(const AttnParams& p, hipStream_t stream) {
-  auto kernel = prefix_rows_kernel<WAVES, SCORES>;
+  auto kernel = prefix_rows_kernel<WAVES, SCORES, KPR>;
   constexpr int kLdsBytes = lds_bytes(WAVES);
   if (kLdsBytes > 64 * 1024) {
     // more than the default 64 KB of dynamic LDS: raise the cap once per device
@@ -439,10 +506,13 @@ hipError_t launch_rows(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_prefix_mfma_rows(const AttnParams& p, hipStream_t stream) {
   if (p.S <= 0) return hipSuccess;
-  if (p.rows_per_group == 256) {
-    return p.want_scores ? launch_rows<8, true>(p, stream) : launch_rows<8, false>(p, stream);
+  const bool big = p.rows_per_group == 256;
+  if (p.d == 64) {
+    if (big) return p.want_scores ? launch_rows<8, true, 2>(p, stream) : launch_rows<8, false, 2>(p, stream);
+    return p.want_scores ? launch_rows<4, true, 2>(p, stream) : launch_rows<4, false, 2>(p, stream);
   }
-  return p.want_scores ? launch_rows<4, true>(p, stream) : launch_rows<4, false>(p, stream);
+  if (big) return p.want_scores ? launch_rows<8, true, 1>(p, stream) : launch_rows<8, false, 1>(p, stream);
+  return p.want_scores ? launch_rows<4, true, 1>(p, stream) : launch_rows<4, false, 1>(p, stream);
 }
 
 }  // namespace specext

@@ -105,6 +105,36 @@ SHAPES = [
 ]
 
 
+# head_dim 64 on the matrix cores (two keys per LDS row): the small draft model's shape (12 heads of 64, no
+# grouping), grouped heads with more than 128 rows per KV head (8-wave kernel), prefixes around the 64-key
+# tile (the shifted last tile with even and odd lengths, with chunk scores spanning its two score blocks)
+D64_SHAPES = [
+    # Hq, Hkv, L, tree, B, splits
+    (12, 12, 1024, "eagle60", 32, 0),
+    (12, 12, 1000, "eagle60", 32, 0),
+    (12, 12, 64, "eagle60", 32, 0),
+    (12, 12, 65, "eagle30", 32, 1),
+    (12, 12, 127, "eagle60", 32, 0),
+    (12, 12, 191, "single", 64, 2),
+    (8, 2, 3001, "eagle60", 32, 0),          # 240 rows per KV head: 8 waves
+    (16, 4, 4096 + 37, "wide128", 64, 5),    # 512 rows per KV head: two row groups
+    (4, 4, 777, "chain16", 32, 3),
+]
+
+
+@pytest.mark.parametrize("Hq,Hkv,L,tree,B,splits", D64_SHAPES)
+def test_head_dim_64_matrix_core_path(hx, Hq, Hkv, L, tree, B, splits):
+    import paper_2505_20776_amd as sx
+    rng = np.random.default_rng(Hq * 100 + L)
+    wl = make_workload(f"d64_{tree}", seed=L + Hq, dtype="bf16", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=64,
+                       prefix_len=L, parent=_tree(tree, rng), chunk_size=B, top_k=4, n_needles=0, value_std=1.0)
+    res, ref_out, ref_lse, ref_scores, _ = _full_check(hx, wl, f"d=64 {tree}", num_splits=splits)
+    # the vector-ALU kernel on the same problem: two independent kernels, one answer
+    valu = hx.run_verify(wl, num_splits=splits, flags=sx.SPECEXT_FLAG_VALU_PREFIX)
+    assert np.abs(valu["out"] - res["out"]).max() <= 2e-2 * np.abs(ref_out).max()
+    assert np.abs(valu["scores"] - res["scores"]).max() <= 1e-4 * ref_scores.max()
+
+
 def _tree(kind, rng):
     return {"eagle60": lambda: eagle_style_tree(60, 6, rng), "eagle30": lambda: eagle_style_tree(30, 5, rng),
             "single": lambda: chain_tree(1),

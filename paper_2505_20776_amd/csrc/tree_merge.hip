@@ -349,6 +349,220 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
   }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// The same result for the hot configuration (head_dim 128, bf16 inputs, fp16 partials,
+// at most 64 splits), with the work of four rows shared by four wavefronts.
+//
+// The kernel above gives a row's whole merge to sixteen lanes of one wave: the launch then
+// has fewer waves than the chip has SIMDs, every wave runs alone on its SIMD and the
+// kernel's duration is the time one wave takes to issue its ~2400 instructions.  Here the
+// four waves of a workgroup serve the same four rows and each takes a quarter of the items
+// of the row's softmax: PER consecutive prefix splits and every fourth node of the ancestor
+// chain.  A wave reduces its items to a partial (max, sum, output) in the usual way, the four
+// partials meet in LDS, and wave w finishes row w.  Per wave the instruction stream is a
+// quarter as long and two waves share a SIMD, so issue time no longer bounds the kernel.
+// Every sum keeps a fixed order: bit-reproducible from run to run.
+constexpr int kShareWaves = 4;
+constexpr int kShareSlot = 132;               // floats per (wave, row) slot: 128 outputs, max, sum, padding
+
+template <int PER>
+__global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(AttnParams p) {
+  constexpr int D = 128, E = 8;
+  constexpr int kThreads = kShareWaves * 64;
+  static_assert(SPECEXT_MAX_TREE <= kThreads, "one parent entry per thread");
+  static_assert(PER >= 1 && PER <= 16, "a group of 16 lanes holds one (max, sum) pair per lane");
+  __shared__ int parent_lds[SPECEXT_MAX_TREE];
+  __shared__ __attribute__((aligned(16))) float slots[kShareWaves][kRowsPerWave][kShareSlot];
+  __shared__ int any_bad;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15;
+  const int rg = lane >> 4;                      // row of the workgroup this group of 16 lanes works for
+  const int grp0 = lane & 48;
+  const int n_rows = p.Hq * p.T;
+
+  // parent[] first, then everything else that depends on nothing; loads return in issue order
+  const int par_reg = tid < p.T ? p.parent[tid] : -1;
+  const int row_raw = blockIdx.x * kRowsPerWave + rg;
+  const bool live = row_raw < n_rows;
+  const int row = live ? row_raw : n_rows - 1;   // groups past the end repeat the last row and store nothing
+  const int g = static_cast<int>((static_cast<float>(row) + 0.5f) * (1.0f / static_cast<float>(p.M)));
+  const int m = row - g * p.M;
+  const int t = static_cast<int>((static_cast<float>(m) + 0.5f) * (1.0f / static_cast<float>(p.G)));
+  const int h = g * p.G + (m - t * p.G);
+
+  // this wave's splits: s_lo .. s_lo + PER - 1; those past the last split read the last one
+  // again and count as empty
+  const int s_lo = wave * PER;
+  const int s_last = p.S - 1;
+  float2 ml = *reinterpret_cast<const float2*>(
+      p.part_ml + (static_cast<int64_t>(min(s_lo + li, s_last)) * n_rows + row) * 2);
+  const bool ml_valid = li < PER && s_lo + li <= s_last;
+  const int64_t split_words = static_cast<int64_t>(n_rows) * D / 2;
+  const uint32_t* po = reinterpret_cast<const uint32_t*>(p.part_o) + (static_cast<int64_t>(row) * D + li * E) / 2;
+  uintx4 raw[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) raw[u] = *reinterpret_cast<const uintx4*>(po + min(s_lo + u, s_last) * split_words);
+  float q[E];
+  load_row_part<E, true>(p.q, t * p.q_st + h * p.q_sh + li * E, q);
+
+  {
+    bool bad = false;
+    if (tid < p.T) {
+      parent_lds[tid] = par_reg;
+      bad = (par_reg >= tid) || (par_reg < -1);
+    }
+    if (blockIdx.x == 0) {
+      // single writer of the status word: 1 if any parent index is not a topological one
+      if (tid == 0) any_bad = 0;
+      __syncthreads();
+      if (bad) any_bad = 1;
+      __syncthreads();
+      if (tid == 0) *p.status = any_bad;
+    } else {
+      __syncthreads();
+    }
+  }
+
+  // Ancestor chain of the row's node (the node itself first).  Every wave walks the whole
+  // chain and keeps the nodes at positions wave, wave + 4, ...; kAnc of them per batch.  A
+  // malformed parent entry ends the walk (the node is then treated as a root).
+  constexpr int kAnc = 2;
+  int a = t;
+  int anc[kAnc];
+  uintx4 kraw[kAnc], vraw[kAnc];
+  auto request_batch = [&]() {
+#pragma unroll
+    for (int u = 0; u < kAnc; ++u) {
+#pragma unroll
+      for (int w = 0; w < kShareWaves; ++w) {
+        if (w == wave) anc[u] = a;
+        if (a >= 0) {
+          const int par = parent_lds[a];
+          a = (par >= a || par < -1) ? -1 : par;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kAnc; ++u) {
+      const int64_t off = g * p.kt_sh + max(anc[u], 0) * p.kt_st + li * E;
+      kraw[u] = *reinterpret_cast<const uintx4*>(static_cast<const uint16_t*>(p.kt) + off);
+      vraw[u] = *reinterpret_cast<const uintx4*>(static_cast<const uint16_t*>(p.vt) + off);
+    }
+  };
+  request_batch();
+
+  // the wave's prefix splits: lane i of a group holds (max, sum) of split s_lo + i
+  if (!ml_valid || !(ml.y > 0.f)) ml = make_float2(-INFINITY, 0.f);        // an empty split contributes nothing
+  float run_max = row16_max(ml.x);
+  const float wgt = ml.y > 0.f ? fast_exp2(ml.x - run_max) : 0.f;
+  float run_sum = row16_sum(ml.y * wgt);
+  float o[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    q[e] *= p.scale_log2;
+    o[e] = 0.f;
+  }
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const float w = lane_read(wgt, grp0 + u);
+#pragma unroll
+    for (int e = 0; e < E / 2; ++e) {
+      const uint32_t word = raw[u][e];
+      const halfx2 hh = __builtin_bit_cast(halfx2, word);
+      o[2 * e] = fmaf(static_cast<float>(hh[0]), w, o[2 * e]);
+      o[2 * e + 1] = fmaf(static_cast<float>(hh[1]), w, o[2 * e + 1]);
+    }
+  }
+
+  // the wave's share of the tree part, one online-softmax step per batch
+  while (true) {
+    float sc[kAnc];
+#pragma unroll
+    for (int u = 0; u < kAnc; ++u) {
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < E / 2; ++e) {
+        const uint32_t word = kraw[u][e];
+        dot = fmaf(q[2 * e], __uint_as_float(word << 16), dot);
+        dot = fmaf(q[2 * e + 1], __uint_as_float(word & 0xffff0000u), dot);
+      }
+      dot = row16_sum(dot);
+      sc[u] = anc[u] >= 0 ? dot : -INFINITY;
+    }
+    float bm = sc[0];
+#pragma unroll
+    for (int u = 1; u < kAnc; ++u) bm = fmaxf(bm, sc[u]);
+    const float new_max = fmaxf(run_max, bm);
+    // nothing seen so far and nothing in this batch: keep the empty state
+    const float alpha = new_max > -INFINITY ? fast_exp2(run_max - new_max) : 1.f;
+    run_max = new_max;
+    run_sum *= alpha;
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[e] *= alpha;
+#pragma unroll
+    for (int u = 0; u < kAnc; ++u) {
+      const float pr = anc[u] >= 0 ? fast_exp2(sc[u] - new_max) : 0.f;
+#pragma unroll
+      for (int e = 0; e < E / 2; ++e) {
+        const uint32_t word = vraw[u][e];
+        o[2 * e] = fmaf(pr, __uint_as_float(word << 16), o[2 * e]);
+        o[2 * e + 1] = fmaf(pr, __uint_as_float(word & 0xffff0000u), o[2 * e + 1]);
+      }
+      run_sum += pr;
+    }
+    if (!__any(a >= 0)) break;
+    request_batch();
+  }
+
+  // the wave's partial goes to LDS; wave w then finishes row w, two output elements per lane
+  {
+    float* slot = &slots[wave][rg][0];
+    *reinterpret_cast<float4*>(slot + li * E) = make_float4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<float4*>(slot + li * E + 4) = make_float4(o[4], o[5], o[6], o[7]);
+    if (li == 0) *reinterpret_cast<float2*>(slot + D) = make_float2(run_max, run_sum);
+  }
+  __syncthreads();
+  const int frow = blockIdx.x * kRowsPerWave + wave;
+  if (frow >= n_rows) return;
+  float2 st[kShareWaves];
+#pragma unroll
+  for (int w = 0; w < kShareWaves; ++w) st[w] = *reinterpret_cast<const float2*>(&slots[w][wave][D]);
+  float top = st[0].x;
+#pragma unroll
+  for (int w = 1; w < kShareWaves; ++w) top = fmaxf(top, st[w].x);     // finite: wave 0 holds the node itself
+  float total = 0.f;
+  float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+  for (int w = 0; w < kShareWaves; ++w) {
+    const float wt = st[w].y > 0.f ? fast_exp2(st[w].x - top) : 0.f;
+    total = fmaf(st[w].y, wt, total);
+    const float2 v = *reinterpret_cast<const float2*>(&slots[w][wave][lane * 2]);
+    acc.x = fmaf(v.x, wt, acc.x);
+    acc.y = fmaf(v.y, wt, acc.y);
+  }
+  const float inv = 1.f / total;
+  const int fg = static_cast<int>((static_cast<float>(frow) + 0.5f) * (1.0f / static_cast<float>(p.M)));
+  const int fm = frow - fg * p.M;
+  const int ft = static_cast<int>((static_cast<float>(fm) + 0.5f) * (1.0f / static_cast<float>(p.G)));
+  const int fh = fg * p.G + (fm - ft * p.G);
+  const int64_t ooff = ft * p.o_st + fh * p.o_sh + lane * 2;
+  if (p.out_dtype == SPECEXT_BF16) {
+    *reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(p.out) + ooff) =
+        static_cast<uint32_t>(float_to_bf16_bits(acc.x * inv)) |
+        (static_cast<uint32_t>(float_to_bf16_bits(acc.y * inv)) << 16);
+  } else {
+    *reinterpret_cast<float2*>(static_cast<float*>(p.out) + ooff) = make_float2(acc.x * inv, acc.y * inv);
+  }
+  if (lane == 0) {
+    const float l2 = top + log2f(total);
+    p.lse2[frow] = l2;
+    if (p.lse) p.lse[fh * p.T + ft] = l2 * kLn2;
+  }
+}
+
 }  // namespace
 
 hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream) {
@@ -358,6 +572,18 @@ hipError_t launch_tree_merge(const AttnParams& p, hipStream_t stream) {
   const bool bf16 = p.in_dtype == SPECEXT_BF16;
   if (p.part_f16 && !(p.d == 128 && bf16)) return hipErrorInvalidValue;
   const bool pre = p.S > 0;
+#ifndef SPECEXT_MERGE_ONE_WAVE_PER_ROWS
+  if (p.part_f16 && p.S >= 1 && p.S <= 16 * kShareWaves) {
+    dim3 shared_block(kShareWaves * 64);
+    const int per = (p.S + kShareWaves - 1) / kShareWaves;       // splits per wave, rounded up to a power of two
+    if (per <= 1) tree_merge_shared_kernel<1><<<grid, shared_block, 0, stream>>>(p);
+    else if (per <= 2) tree_merge_shared_kernel<2><<<grid, shared_block, 0, stream>>>(p);
+    else if (per <= 4) tree_merge_shared_kernel<4><<<grid, shared_block, 0, stream>>>(p);
+    else if (per <= 8) tree_merge_shared_kernel<8><<<grid, shared_block, 0, stream>>>(p);
+    else tree_merge_shared_kernel<16><<<grid, shared_block, 0, stream>>>(p);
+    return hipGetLastError();
+  }
+#endif
 #define SPECEXT_LAUNCH(D_, BF_, F16_)                                                              \
   do {                                                                                             \
     if (pre) tree_merge_kernel<D_, BF_, F16_, true><<<grid, block, 0, stream>>>(p);                \

@@ -72,7 +72,7 @@ def test_llama_layer_2k(hx, sharp):
     assert set(wl.needle_chunks) <= set(int(i) for i in sel)
 
 
-@pytest.mark.parametrize("splits", [1, 2, 5, 32])
+@pytest.mark.parametrize("splits", [1, 2, 5, 13, 27, 32, 47, 64])
 def test_llama_layer_split_counts(hx, splits):
     wl = config_workload(2, sharp=True, prefix_len=2048 - 37)
     _full_check(hx, wl, f"cfg2 ragged splits={splits}", num_splits=splits)

@@ -184,70 +184,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
   }
 }
 
-// Short inputs (n <= kRankMax, one key per thread): every thread ranks its own key
-// against all the others, which sit in LDS and are read four at a time by broadcast.
-// rank(i) = #{j : key_j > key_i} + #{j < i : key_j == key_i} (ties go to the lower
-// index); a key is kept when rank < k.  Two barriers in all, against the one per key
-// bit of the radix search above.  The output order comes from ballot prefix counts.
+// Short inputs (n <= kRankMax) get one key per thread and the byte-wise selection below.
 constexpr int kRankMax = 1024;
 
-// One workgroup (blockDim.x a multiple of 256, at least n threads), thread i holding the score
+// One workgroup (blockDim.x a multiple of 64, at least n threads), thread i holding the score
 // of chunk i.  The key of the k-th largest score is found a byte at a time from the top:
 // a 256-bin histogram (LDS atomics) of the keys that match the bytes fixed so far, a
 // suffix scan over the bins, and the bin that holds the k-th key fixes the next byte - four
-// rounds instead of one compare of every key with every other.  Keys above the threshold
-// are all taken; of the keys equal to it the lowest-indexed ones fill what is left; two
-// block scans in index order give the ascending output.
+// rounds instead of one compare of every key with every other.  Every wave does the scan
+// for itself (four bins per lane), so a round costs one barrier.  Keys above the threshold
+// are all taken; of the keys equal to it the lowest-indexed ones fill what is left; ballots
+// and one exchange of per-wave counts give the ascending output.
 struct RadixLds {
-  int hist[256];
-  int wave_sums[kSelThreads / 64];
-  int sel_bin, sel_need;
+  __attribute__((aligned(16))) int hist[4][256];     // one histogram per round, all cleared up front
+  int wave_counts[kSelThreads / 64][2];              // per wave: keys above the threshold, keys equal to it
 };
 
 __device__ __forceinline__ void radix_select_and_write(float score, int n, int k, int* __restrict__ idx_out,
                                                        int* __restrict__ n_out, RadixLds& sh) {
-  const int i = threadIdx.x;
-  const int k_eff = min(k, n);
-  if (i == 0) *n_out = k_eff;
-  for (int u = k_eff + i; u < k; u += blockDim.x) idx_out[u] = -1;
-  if (k_eff == 0) return;
-  const bool live = i < n;
-  const uint32_t key = live ? orderable(score) : 0u;
-  uint32_t prefix = 0;           // the bytes of the threshold fixed so far (higher bytes first)
-  int need = k_eff;              // keys still to take among those that match `prefix` in the fixed bytes
-#pragma unroll
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    if (i < 256) sh.hist[i] = 0;
-    __syncthreads();
-    const bool match = live && (shift == 24 || (key >> (shift + 8)) == (prefix >> (shift + 8)));
-    if (match) atomicAdd(&sh.hist[(key >> shift) & 255u], 1);
-    __syncthreads();
-    // thread t < 256 looks at bin 255 - t: `above` = keys in higher bins
-    const int mine = i < 256 ? sh.hist[255 - i] : 0;
-    int total;
-    const int above = block_exclusive_scan(mine, sh.wave_sums, total);
-    if (i < 256 && above < need && need <= above + mine) {
-      sh.sel_bin = 255 - i;
-      sh.sel_need = need - above;
-    }
-    __syncthreads();
-    prefix |= static_cast<uint32_t>(sh.sel_bin) << shift;
-    need = sh.sel_need;
-  }
-  // prefix is the k-th largest key; `need` of the keys equal to it are taken, lowest index first
-  const int is_tie = (live && key == prefix) ? 1 : 0;
-  int tie_total;
-  const int tie_rank = block_exclusive_scan(is_tie, sh.wave_sums, tie_total);
-  const int take = (live && key > prefix) ? 1 : (is_tie & (tie_rank < need ? 1 : 0));
-  int take_total;
-  const int pos = block_exclusive_scan(take, sh.wave_sums, take_total);
-  if (take) idx_out[pos] = i;
-}
-
-// One workgroup, thread i holding the score of chunk i (threads past n hold nothing): ranks
-// the scores through `keys` / `wave_takes` (LDS) and writes idx_out / n_out.
-__device__ __forceinline__ void rank_and_write(float score, int n, int k, int* __restrict__ idx_out,
-                                               int* __restrict__ n_out, uint32_t* keys, int* wave_takes) {
   const int i = threadIdx.x;
   const int lane = i & 63;
   const int wave = i >> 6;
@@ -255,48 +209,70 @@ __device__ __forceinline__ void rank_and_write(float score, int n, int k, int* _
   if (i == 0) *n_out = k_eff;
   for (int u = k_eff + i; u < k; u += blockDim.x) idx_out[u] = -1;
   if (k_eff == 0) return;
-  // keys are kept >= 1 so that "key - 1" below cannot wrap; padding slots hold 0, below every key
-  const uint32_t mine = i < n ? max(orderable(score), 1u) : 0u;
-  keys[i] = mine;
+  const bool live = i < n;
+  const uint32_t key = live ? orderable(score) : 0u;
+  for (int u = i; u < 4 * 256; u += blockDim.x) (&sh.hist[0][0])[u] = 0;
   __syncthreads();
-  const int n4 = (n + 3) & ~3;                   // blockDim.x is a multiple of 64, so the padding exists
-  // key_j counts against thread i when key_j > key_i, or key_j == key_i and j < i: that is
-  // key_j > key_i - 1 for j < i and key_j > key_i for j > i.  For the j of earlier waves the
-  // first form holds for the whole wave, for those of later waves the second; only inside
-  // the thread's own wave does it depend on the lane.
-  const uint32_t below = mine - 1u;
-  int rank = 0;
-  const int own_lo = wave * 64, own_hi = own_lo + 64;
-  for (int j = 0; j < min(own_lo, n4); j += 4) {
-    const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
-    rank += (kj.x > below) + (kj.y > below) + (kj.z > below) + (kj.w > below);
+  uint32_t prefix = 0;           // the bytes of the threshold fixed so far (higher bytes first)
+  int need = k_eff;              // keys still to take among those that match `prefix` in the fixed bytes
+#pragma unroll
+  for (int round = 0; round < 4; ++round) {
+    const int shift = 24 - 8 * round;
+    const bool match = live && (round == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8)));
+    if (match) atomicAdd(&sh.hist[round][(key >> shift) & 255u], 1);
+    __syncthreads();
+    // lane l looks at bins 255 - 4l (first) down to 252 - 4l; `above` = keys in higher bins
+    const int4 h = *reinterpret_cast<const int4*>(&sh.hist[round][252 - 4 * lane]);
+    const int bins[4] = {h.w, h.z, h.y, h.x};
+    const int mine = (h.x + h.y) + (h.z + h.w);
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    int above = incl - mine;
+    int bin = -1, left = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (above < need && need <= above + bins[j]) {
+        bin = 255 - 4 * lane - j;
+        left = need - above;
+      }
+      above += bins[j];
+    }
+    // exactly one lane found the bin (1 <= need <= number of matching keys)
+    const int src = __ffsll(static_cast<long long>(__ballot(bin >= 0))) - 1;
+    prefix |= static_cast<uint32_t>(__shfl(bin, src, 64)) << shift;
+    need = __shfl(left, src, 64);
   }
-  for (int j = own_lo; j < min(own_hi, n4); j += 4) {
-    const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
-    rank += (kj.x > (j < i ? below : mine)) + (kj.y > (j + 1 < i ? below : mine)) + (kj.z > (j + 2 < i ? below : mine)) +
-            (kj.w > (j + 3 < i ? below : mine));
+  // prefix is the k-th largest key; `need` of the keys equal to it are taken, lowest index first
+  const bool greater = live && key > prefix;
+  const bool is_tie = live && key == prefix;
+  const uint64_t bal_greater = __ballot(greater), bal_tie = __ballot(is_tie);
+  if (lane == 0) {
+    sh.wave_counts[wave][0] = __popcll(bal_greater);
+    sh.wave_counts[wave][1] = __popcll(bal_tie);
   }
-  for (int j = own_hi; j < n4; j += 4) {
-    const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
-    rank += (kj.x > mine) + (kj.y > mine) + (kj.z > mine) + (kj.w > mine);
-  }
-  const bool take = i < n && rank < k_eff;
-  const uint64_t bal = __ballot(take);
-  if (lane == 0) wave_takes[wave] = __popcll(bal);
   __syncthreads();
-  if (take) {
-    int pos = __popcll(bal & ((uint64_t{1} << lane) - 1));
-    for (int w = 0; w < wave; ++w) pos += wave_takes[w];
-    idx_out[pos] = i;
+  int ties_before = 0, pos = 0;
+  for (int w = 0; w < wave; ++w) {
+    const int gr = sh.wave_counts[w][0], ti = sh.wave_counts[w][1];
+    pos += gr + min(max(need - ties_before, 0), ti);
+    ties_before += ti;
   }
+  const uint64_t lower = (uint64_t{1} << lane) - 1;
+  const int tie_rank = ties_before + __popcll(bal_tie & lower);
+  const bool take = greater || (is_tie && tie_rank < need);
+  const uint64_t bal_take = __ballot(take);
+  if (take) idx_out[pos + __popcll(bal_take & lower)] = i;
 }
 
-__global__ __launch_bounds__(kRankMax) void select_rank_kernel(const float* __restrict__ scores, int n, int k,
+__global__ __launch_bounds__(kRankMax) void select_short_kernel(const float* __restrict__ scores, int n, int k,
                                                               int* __restrict__ idx_out, int* __restrict__ n_out) {
-  __shared__ __attribute__((aligned(16))) uint32_t keys[kRankMax];
-  __shared__ int wave_takes[kRankMax / 64];
+  __shared__ RadixLds radix;
   const int i = threadIdx.x;
-  rank_and_write(i < n ? scores[i] : 0.f, n, k, idx_out, n_out, keys, wave_takes);
+  radix_select_and_write(i < n ? scores[i] : 0.f, n, k, idx_out, n_out, radix);
 }
 
 // Chunk scores of one tree row and the top-k over them in one launch (at most kRankMax
@@ -319,39 +295,52 @@ __global__ __launch_bounds__(kRankMax) void score_select_kernel(AttnParams p, in
   const int part = threadIdx.x & 3;
   const int per_chunk = p.B / p.score_gran;
   constexpr int kHeadsAtOnce = 8;                // heads of one thread whose loads are in flight together
+  constexpr int kChunksAtOnce = 2;               // chunks of one thread, likewise
   const int chunks_per_pass = blockDim.x / 4;
-  for (int c0 = 0; c0 < p.C; c0 += chunks_per_pass) {
-    const int c = c0 + (threadIdx.x >> 2);
-    float acc = 0.f;
-    if (c < p.C) {
-      const int sub_lo = c * per_chunk;
-      const int sub_hi = min(sub_lo + per_chunk, p.n_sub);
-      for (int hb = part; hb < p.Hq; hb += 4 * kHeadsAtOnce) {
-        float l2[kHeadsAtOnce];
-        float2 first[kHeadsAtOnce];
-        const float* src[kHeadsAtOnce];
+  for (int c0 = 0; c0 < p.C; c0 += kChunksAtOnce * chunks_per_pass) {
+    int cs[kChunksAtOnce], sub_lo[kChunksAtOnce], sub_hi[kChunksAtOnce];
+    float acc[kChunksAtOnce];
 #pragma unroll
-        for (int u = 0; u < kHeadsAtOnce; ++u) {
-          const int h = min(hb + 4 * u, p.Hq - 1);               // heads past the end re-read the last one, unused
-          const int g = h / p.G;
-          const int m = t * p.G + (h - g * p.G);
-          l2[u] = p.lse2[g * p.M + m];
-          src[u] = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sub_lo) * p.M + m) * 2;
-          first[u] = *reinterpret_cast<const float2*>(src[u]);
+    for (int j = 0; j < kChunksAtOnce; ++j) {
+      cs[j] = c0 + j * chunks_per_pass + (threadIdx.x >> 2);
+      const int cl = min(cs[j], p.C - 1);                        // chunks past the end re-read the last one, unused
+      sub_lo[j] = cl * per_chunk;
+      sub_hi[j] = min(sub_lo[j] + per_chunk, p.n_sub);
+      acc[j] = 0.f;
+    }
+    for (int hb = part; hb < p.Hq; hb += 4 * kHeadsAtOnce) {
+      float l2[kHeadsAtOnce];
+      float2 first[kChunksAtOnce][kHeadsAtOnce];
+      const float* src[kChunksAtOnce][kHeadsAtOnce];
+#pragma unroll
+      for (int u = 0; u < kHeadsAtOnce; ++u) {
+        const int h = min(hb + 4 * u, p.Hq - 1);                 // heads past the end re-read the last one, unused
+        const int g = h / p.G;
+        const int m = t * p.G + (h - g * p.G);
+        l2[u] = p.lse2[g * p.M + m];
+#pragma unroll
+        for (int j = 0; j < kChunksAtOnce; ++j) {
+          src[j][u] = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + sub_lo[j]) * p.M + m) * 2;
+          first[j][u] = *reinterpret_cast<const float2*>(src[j][u]);
         }
+      }
+#pragma unroll
+      for (int j = 0; j < kChunksAtOnce; ++j) {
 #pragma unroll
         for (int u = 0; u < kHeadsAtOnce; ++u) {
           if (hb + 4 * u < p.Hq) {
-            acc += first[u].x * exp2f(first[u].y - l2[u]);
-            for (int sb = sub_lo + 1; sb < sub_hi; ++sb) {
-              const float2 cp = *reinterpret_cast<const float2*>(src[u] + static_cast<int64_t>(sb - sub_lo) * p.M * 2);
-              acc += cp.x * exp2f(cp.y - l2[u]);
+            acc[j] += first[j][u].x * exp2f(first[j][u].y - l2[u]);
+            for (int sb = sub_lo[j] + 1; sb < sub_hi[j]; ++sb) {
+              const float2 cp = *reinterpret_cast<const float2*>(src[j][u] + static_cast<int64_t>(sb - sub_lo[j]) * p.M * 2);
+              acc[j] += cp.x * exp2f(cp.y - l2[u]);
             }
           }
         }
       }
     }
-    if (c < p.C) partial[c][part] = acc;
+#pragma unroll
+    for (int j = 0; j < kChunksAtOnce; ++j)
+      if (cs[j] < p.C) partial[cs[j]][part] = acc[j];
   }
   __syncthreads();
   const int c = threadIdx.x;
@@ -467,7 +456,9 @@ hipError_t launch_score_select(const AttnParams& p, int32_t score_row, const int
                                const int32_t* row_count, int32_t k, float* scores, int32_t* idx_out, int32_t* n_out,
                                hipStream_t stream) {
   if (p.C > kRankMax) return hipErrorInvalidValue;
-  const int threads = p.C <= 256 ? 256 : ((p.C + 255) / 256) * 256;       // one key per thread, all 256 bins covered
+  // at least one thread per chunk (selection), up to eight (scores: two chunks in flight per thread, four threads
+  // per chunk, so that 1024 threads take in 512 chunks in one pass)
+  const int threads = p.C <= 128 ? 256 : p.C <= 256 ? 512 : 1024;
   score_select_kernel<<<dim3(1), dim3(threads), 0, stream>>>(p, score_row, row_path, row_count, k, scores, idx_out, n_out);
   return hipGetLastError();
 }
@@ -477,7 +468,7 @@ hipError_t launch_select_chunks(const float* scores, int32_t n_chunks, int32_t k
   // a small input needs only as many waves as it has scores (fewer waves, cheaper barriers)
   const int threads = n_chunks >= kSelThreads ? kSelThreads : ((n_chunks + 63) / 64) * 64;
   if (n_chunks <= kRankMax) {
-    select_rank_kernel<<<dim3(1), dim3(threads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
+    select_short_kernel<<<dim3(1), dim3(threads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
   } else {
     select_kernel<<<dim3(1), dim3(threads), 0, stream>>>(scores, n_chunks, k, idx_out, n_out);
   }

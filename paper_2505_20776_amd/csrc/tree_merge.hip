@@ -363,7 +363,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
 // partials meet in LDS, and wave w finishes row w.  Per wave the instruction stream is a
 // quarter as long and two waves share a SIMD, so issue time no longer bounds the kernel.
 // Every sum keeps a fixed order: bit-reproducible from run to run.
-constexpr int kShareWaves = 4;
+constexpr int kShareWaves = 4;               // 8 measured no faster
 constexpr int kShareSlot = 132;               // floats per (wave, row) slot: 128 outputs, max, sum, padding
 
 template <int PER>
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
   // Ancestor chain of the row's node (the node itself first).  Every wave walks the whole
   // chain and keeps the nodes at positions wave, wave + 4, ...; kAnc of them per batch.  A
   // malformed parent entry ends the walk (the node is then treated as a root).
-  constexpr int kAnc = 2;
+  constexpr int kAnc = 8 / kShareWaves;
   int a = t;
   int anc[kAnc];
   uintx4 kraw[kAnc], vraw[kAnc];
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
   }
   __syncthreads();
   const int frow = blockIdx.x * kRowsPerWave + wave;
-  if (frow >= n_rows) return;
+  if (wave >= kRowsPerWave || frow >= n_rows) return;
   float2 st[kShareWaves];
 #pragma unroll
   for (int w = 0; w < kShareWaves; ++w) st[w] = *reinterpret_cast<const float2*>(&slots[w][wave][D]);

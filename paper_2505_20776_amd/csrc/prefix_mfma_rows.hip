@@ -249,11 +249,21 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   const int score_step = p.M * 2;
   if (SCORES) score_base = p.chunk_part + ((static_cast<int64_t>(g) * p.n_sub + key_lo / kTile) * p.M + min(m, p.M - 1)) * 2;
 
-  // One tile: logits, online softmax (one query row per lane pair, the reference moves
-  // lazily), O^T += V^T P^T.  SLOT is the tile's ring slot.
-  auto tile = [&](auto slot_c, int j) {
+  // One tile in two parts.  Front: the logits (matrix pipe) and the V^T fragments, everything
+  // the tile needs from its ring slot SLOT.  Back: online softmax (vector ALU; one query row
+  // per lane pair, the reference moves lazily) and O^T += V^T P^T (matrix pipe) from
+  // registers alone.  The two waves of a SIMD leave every barrier together, and with the
+  // same instruction stream they would want the matrix pipe at the same time and the
+  // vector ALU at the same time, one unit idling while the other is contended.  So one of
+  // the two runs its loop rotated by half a tile - back of the tile before, then front of
+  // this one - and its softmax falls on the other's matrix products.
+  // Waves w and w + 4 of a workgroup share a SIMD (measured: rotating the upper four gains,
+  // rotating every other wave or every other pair loses).
+  const bool rotated = (wave & 4) != 0;
+  floatx16 s[KPR];               // the tile's logits, then its probabilities
+  bf16x8 vf[4][2];               // the tile's V^T fragments
+  auto tile_front = [&](auto slot_c) __attribute__((always_inline)) {
     constexpr int slot = decltype(slot_c)::value * kTileBytes;
-    floatx16 s[KPR];
 #pragma unroll
     for (int kp = 0; kp < KPR; ++kp) {
       s[kp] = zero16;
@@ -263,7 +273,6 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
         s[kp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[ks], s[kp], 0, 0, 0);
       }
     }
-    bf16x8 vf[4][2];             // the tile's V^T fragments
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
       const unsigned char* col = lds + v_rd[db] + slot;
@@ -275,6 +284,8 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
         vf[db][jj] = __builtin_bit_cast(bf16x8, both);
       }
     }
+  };
+  auto tile_back = [&](int j) __attribute__((always_inline)) {
     const int key0 = tile_key0(j);
     const int first_key = tile_first_row(j);
     // register r of s[kp] holds key first_key + KPR * (4*hf + 8*(r/4) + r%4) + kp
@@ -359,34 +370,50 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   // stage s is read every wave waits for its own share of it and meets the others at a
   // barrier; behind that barrier every wave has also left stage s-1, whose ring stage
   // takes the loads of stage s + kStages - 1.  Between two barriers the waves run free.
-  for (int s0 = 0; s0 < n_stages; s0 += kStages) {
-    static_for<0, kStages>([&](auto u_c) {
-      constexpr int u = decltype(u_c)::value;
-      const int s = s0 + u;
-      if (s < n_stages) {
-        if (s == 0) {
-          wait_vmcnt_even(younger_than_stage(0));        // also covers the wave's own queries
+  // The loop exists twice, once per order of the two parts, so that each order gets its
+  // own register allocation.
+  auto key_loop = [&](auto rot_c) __attribute__((always_inline)) {
+    constexpr bool kRot = decltype(rot_c)::value;
+    for (int s0 = 0; s0 < n_stages; s0 += kStages) {
+      static_for<0, kStages>([&](auto u_c) {
+        constexpr int u = decltype(u_c)::value;
+        const int s = s0 + u;
+        if (s < n_stages) {
+          if (s == 0) {
+            wait_vmcnt_even(younger_than_stage(0));        // also covers the wave's own queries
 #pragma unroll
-          for (int ks = 0; ks < kQSteps; ++ks)
-            qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(priv + k_rd[ks]));
-        } else if ((s + kStages - 1) * kStageTiles <= n) {
-          asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kLoadsPerTile * kStageTiles * (kStages - 2)) : "memory");
-        } else {
-          wait_vmcnt_even(younger_than_stage(s));
-        }
-        lds_barrier();
+            for (int ks = 0; ks < kQSteps; ++ks)
+              qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(priv + k_rd[ks]));
+          } else if ((s + kStages - 1) * kStageTiles <= n) {
+            asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kLoadsPerTile * kStageTiles * (kStages - 2)) : "memory");
+          } else {
+            wait_vmcnt_even(younger_than_stage(s));
+          }
+          lds_barrier();
 #ifdef SPECEXT_TAIL_STAMPS
-        if (s == 0) stamp_first = wall_clock64();
+          if (s == 0) stamp_first = wall_clock64();
 #endif
-        if (s + kStages - 1 < n_stages) issue_stage(ic<(u + kStages - 1) % kStages>{}, s + kStages - 1);
-        static_for<0, kStageTiles>([&](auto i_c) {
-          constexpr int i = decltype(i_c)::value;
-          const int j = s * kStageTiles + i;
-          if (j < n && wave_live) tile(ic<u * kStageTiles + i>{}, j);
-        });
-      }
-    });
-  }
+          if (s + kStages - 1 < n_stages) issue_stage(ic<(u + kStages - 1) % kStages>{}, s + kStages - 1);
+          static_for<0, kStageTiles>([&](auto i_c) {
+            constexpr int i = decltype(i_c)::value;
+            const int j = s * kStageTiles + i;
+            if (j < n && wave_live) {
+              if constexpr (kRot) {
+                if (j > 0) tile_back(j - 1);
+                tile_front(ic<u * kStageTiles + i>{});
+              } else {
+                tile_front(ic<u * kStageTiles + i>{});
+                tile_back(j);
+              }
+            }
+          });
+        }
+      });
+    }
+    if (kRot && wave_live) tile_back(n - 1);
+  };
+  if (rotated) key_loop(std::true_type{});
+  else key_loop(std::false_type{});
 
 #ifdef SPECEXT_TAIL_STAMPS
   stamp_loop = wall_clock64();

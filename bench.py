@@ -83,6 +83,10 @@ def parse_args():
     ap.add_argument("--no-calibrate", action="store_true",
                     help="skip the two calibration kernels (pure HBM read stream, pure bf16 matrix-core loop) whose rates "
                          "are reported as measured_* next to the published peaks")
+    ap.add_argument("--operands", choices=["recipe", "zeros", "unit"], default="recipe",
+                    help="values of Q, K and V: recipe (default; N(0, 1/d), the workload the metric is quoted on), "
+                         "zeros or N(0, 1) - the same instruction stream on other bits, to show how much of the time is "
+                         "the power management's answer to the data; such a line is labelled and is not the metric")
     ap.add_argument("--cpu-layers", type=int, default=32, help="layers the oracle is timed on (32 = the whole step, about 10 s)")
     return ap.parse_args()
 
@@ -124,7 +128,10 @@ def main():
     std = 1.0 / np.sqrt(d)
 
     def randn(*shape):
-        return (torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+        if args.operands == "zeros":
+            return torch.zeros(*shape, device=dev, dtype=torch.bfloat16)
+        scale = 1.0 if args.operands == "unit" else std
+        return (torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32) * scale).to(torch.bfloat16)
 
     q = [randn(T, Hq, d) for _ in range(n_layers)]
     kp = [randn(Hkv, L, d) for _ in range(n_layers)]
@@ -269,7 +276,8 @@ def main():
     achieved_tf = flops_per_launch / (prefix_us * 1e-6) / 1e12
     step_us = ms_per_step * 1e3
     gather_bytes = 2 * 2 * Hkv * cap * d * 2                   # K and V, read + written
-    default_workload = args.config == "4" and L == 16384 and Hkv == 8 and args.num_splits == 0 and args.merge == "two-launch"
+    default_workload = (args.config == "4" and L == 16384 and Hkv == 8 and args.num_splits == 0 and
+                        args.merge == "two-launch" and args.operands == "recipe")
     traffic = measured_traffic() if default_workload else None
     result = {
         "metric": "us per verification step (all layers) at 16K prefix" if (args.config == "4" and L == 16384 and Hkv == 8)
@@ -284,7 +292,8 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic" if args.operands == "recipe" else
+                f"synthetic, {args.operands} operands: a probe of data-dependent power, not the metric's workload",
         "config": {
             "workload": f"config {args.config}: {n_layers} layers x (Hq={Hq}, Hkv={Hkv}, d={d}) bf16, prefix {L}, {T}-node tree, "
                         f"chunk {B}, top-{topk} of {n_chunks}, draft gather 1x{Hkv}x{cap}x{d}"

@@ -246,6 +246,24 @@ def test_malformed_parent_sets_status(hx):
     assert np.isfinite(res["out"]).all()
     wl.parent[3] = 1
     assert hx.run_verify(wl)["status"] == 0
+    # the same on a Llama-shaped bf16 layer (matrix-core prefix kernel, fp16 partials, merge shared by four waves):
+    # the bad entry ends that node's ancestor walk, everything stays finite, nothing else changes
+    wl = config_workload(2, prefix_len=777)
+    good = hx.run_verify(wl)
+    assert good["status"] == 0
+    before = wl.parent.copy()
+    wl.parent = wl.parent.copy(); wl.parent[7] = 9
+    bad = hx.run_verify(wl)
+    assert bad["status"] == 1 and np.isfinite(bad["out"]).all() and np.isfinite(bad["lse"]).all()
+    walks_through_7 = np.zeros(wl.n_tree, dtype=bool)
+    for t in range(wl.n_tree):
+        a = t
+        while a >= 0:
+            if a == 7:
+                walks_through_7[t] = True
+                break
+            a = int(before[a])
+    assert (bad["out"][~walks_through_7] == good["out"][~walks_through_7]).all()
 
 
 def test_run_to_run_bit_identical(hx):
@@ -322,6 +340,15 @@ def test_select_ties_and_signs(hx):
     s = np.full(100, 0.25, dtype=np.float32)
     sel, _, _ = hx.run_select(s, 10)
     assert list(sel) == list(range(10))
+    # keys that differ only in their lowest byte, in their lowest two bytes, and across the sign
+    base = np.float32(1.0).view(np.uint32)
+    for spread, n in ((7, 900), (70000, 1024), (3, 130)):
+        bits = (base + rng.integers(0, spread, size=n)).astype(np.uint32)
+        s = bits.view(np.float32).copy()
+        s[::5] *= -1.0
+        for k in (1, 17, n // 2, n - 1):
+            sel, _, _ = hx.run_select(s, k)
+            assert list(sel) == list(orc.select_chunks(s, k)), (spread, n, k)
 
 
 # --------------------------------------------------------------------------

@@ -254,11 +254,14 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   // per lane pair, the reference moves lazily) and O^T += V^T P^T (matrix pipe) from
   // registers alone.  The two waves of a SIMD leave every barrier together, and with the
   // same instruction stream they would want the matrix pipe at the same time and the
-  // vector ALU at the same time, one unit idling while the other is contended.  So one of
-  // the two runs its loop rotated by half a tile - back of the tile before, then front of
-  // this one - and its softmax falls on the other's matrix products.
+  // vector ALU at the same time, one unit idling while the other is contended.  So the two
+  // take their steps in different orders behind a barrier, each with one long matrix
+  // phase and one vector phase that fall on the other's vector and matrix phase:
+  //   upper wave:  softmax of the tile before | its second product, this tile's logits
+  //   lower wave:  second product of the tile before, this tile's logits | its softmax
   // Waves w and w + 4 of a workgroup share a SIMD (measured: rotating the upper four gains,
-  // rotating every other wave or every other pair loses).
+  // rotating every other wave or every other pair loses).  In a workgroup of four waves
+  // every wave has its SIMD to itself and keeps the plain order.
   const bool rotated = (wave & 4) != 0;
   floatx16 s[KPR];               // the tile's logits, then its probabilities
   bf16x8 vf[4][2];               // the tile's V^T fragments
@@ -285,7 +288,8 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       }
     }
   };
-  auto tile_back = [&](int j) __attribute__((always_inline)) {
+  bf16x8 pf[KPR][2];             // the tile's probabilities as the second product takes them
+  auto tile_softmax = [&](int j) __attribute__((always_inline)) {
     const int key0 = tile_key0(j);
     const int first_key = tile_first_row(j);
     // register r of s[kp] holds key first_key + KPR * (4*hf + 8*(r/4) + r%4) + kp
@@ -350,12 +354,13 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
         }
       }
     }
-    bf16x8 pf[KPR][2];
 #pragma unroll
     for (int kp = 0; kp < KPR; ++kp) {
       pf[kp][0] = pack8(s[kp], 0);
       pf[kp][1] = pack8(s[kp], 8);
     }
+  };
+  auto tile_second_product = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int db = 0; db < kOBlocks; ++db) {
 #pragma unroll
@@ -365,15 +370,21 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       }
     }
   };
+  auto tile_back = [&](int j) __attribute__((always_inline)) {
+    tile_softmax(j);
+    tile_second_product();
+  };
 
   // Each wave's loads form the sequence (K, V of tile 0), (K, V of tile 1), ...  Before
   // stage s is read every wave waits for its own share of it and meets the others at a
   // barrier; behind that barrier every wave has also left stage s-1, whose ring stage
   // takes the loads of stage s + kStages - 1.  Between two barriers the waves run free.
-  // The loop exists twice, once per order of the two parts, so that each order gets its
-  // own register allocation.
-  auto key_loop = [&](auto rot_c) __attribute__((always_inline)) {
-    constexpr bool kRot = decltype(rot_c)::value;
+  // The loop exists once per order of the steps, so that each order gets its own register
+  // allocation.
+  auto key_loop = [&](auto order_c) __attribute__((always_inline)) {
+    // 0: front, back; 1: back of the tile before, front; 2: second product of the tile before, front, softmax
+    constexpr int kOrder = decltype(order_c)::value;
+    constexpr bool kRot = kOrder == 1;
     for (int s0 = 0; s0 < n_stages; s0 += kStages) {
       static_for<0, kStages>([&](auto u_c) {
         constexpr int u = decltype(u_c)::value;
@@ -398,7 +409,11 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
             constexpr int i = decltype(i_c)::value;
             const int j = s * kStageTiles + i;
             if (j < n && wave_live) {
-              if constexpr (kRot) {
+              if constexpr (kOrder == 2) {
+                if (j > 0) tile_second_product();
+                tile_front(ic<u * kStageTiles + i>{});
+                tile_softmax(j);
+              } else if constexpr (kRot) {
                 if (j > 0) tile_back(j - 1);
                 tile_front(ic<u * kStageTiles + i>{});
               } else {
@@ -411,9 +426,10 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       });
     }
     if (kRot && wave_live) tile_back(n - 1);
+    if (kOrder == 2 && wave_live) tile_second_product();
   };
-  if (rotated) key_loop(std::true_type{});
-  else key_loop(std::false_type{});
+  if (rotated) key_loop(ic<1>{});
+  else key_loop(ic<(WAVES == 8 ? 2 : 0)>{});
 
 #ifdef SPECEXT_TAIL_STAMPS
   stamp_loop = wall_clock64();

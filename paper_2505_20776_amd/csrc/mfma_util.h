@@ -17,6 +17,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t uintx2;
 typedef __attribute__((ext_vector_type(2))) _Float16 halfx2;
 typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
 typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) uintx4 lds_uintx4;
 
 // The running reference of a row only moves when a tile's max exceeds it by more
 // than this many powers of two, so exp2(s - ref) stays below 2^kLazyLog2.

@@ -229,6 +229,20 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
     v_rd[db] = kRing * kTileBytes + v_key_in * kRowBytes + ((db ^ v_q4) << 6) + ((2 * grp_col + ((li & 3) >> 1)) << 4) +
                ((li & 1) << 3);
 
+  // The operand reads of the loop take these as LDS addresses plus the ring slot's immediate; pinned
+  // in registers so that the compiler does not rebuild each one with an addition per use.
+  unsigned k_addr[8], v_addr[4];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    k_addr[ks] = kring_lds + k_rd[ks];
+    asm volatile("" : "+v"(k_addr[ks]));
+  }
+#pragma unroll
+  for (int db = 0; db < 4; ++db) {
+    v_addr[db] = kring_lds + v_rd[db];
+    asm volatile("" : "+v"(v_addr[db]));
+  }
+
   // queries: B operand of S^T (lane = row c32, 8 consecutive d per k-step), read from
   // the private area once the first wait below has passed
   bf16x8 qf[kQSteps];
@@ -272,17 +286,17 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
       s[kp] = zero16;
 #pragma unroll
       for (int ks = 0; ks < kQSteps; ++ks) {
-        const uintx4 kw = *reinterpret_cast<const uintx4*>(lds + k_rd[ks + kp * kQSteps] + slot);
+        const uintx4 kw = *reinterpret_cast<const lds_uintx4*>(static_cast<uintptr_t>(k_addr[ks + kp * kQSteps] + slot));
         s[kp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[ks], s[kp], 0, 0, 0);
       }
     }
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
-      const unsigned char* col = lds + v_rd[db] + slot;
+      const unsigned col = v_addr[db] + slot;
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(col + (16 * jj) * kRowBytes));
-        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)(col + (16 * jj + 8) * kRowBytes));
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)static_cast<uintptr_t>(col + (16 * jj) * kRowBytes));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4*)static_cast<uintptr_t>(col + (16 * jj + 8) * kRowBytes));
         const shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         vf[db][jj] = __builtin_bit_cast(bf16x8, both);
       }

@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--config", choices=["2", "3", "4", "5wide", "5chain", "draft", "draft68m"], default="4",
                     help="numbered workload: 4 (default) = 32 layers at a 16K prefix, the headline metric; 2 / 3 / 5 = "
                          "the single-layer shapes (2K, 8K, 32K-37 with a 128-node wide tree or a 16-node chain), run "
-                         "over enough distinct K/V copies (>= 300 MB) that every launch streams cold (a second figure, "
+                         "over enough distinct K/V copies (>= 768 MB) that every launch streams cold (a second figure, "
                          "labelled hot, comes from one copy that stays in the caches); draft = the draft model's side "
                          "(Sec. 3.2.1): one EAGLE-style layer of the same shape over a compacted working cache of "
                          "2048 tokens; draft68m = a Vicuna-68M-shaped draft layer (12 heads of 64, no grouping) over "
@@ -120,7 +120,10 @@ def main():
     T = len(parent_np)
     layer_bytes = 2 * Hkv * L * d * 2
     single = args.config != "4"
-    n_layers = args.layers or (32 if args.config == "4" else -(-300_000_000 // layer_bytes))
+    # Cold means cold: the distinct K/V copies of a step add up to three times the 256 MB last-level cache (with
+    # little more than one cache size, launches that follow one another directly still found part of their K/V there)
+    cold_layers = -(-768_000_000 // layer_bytes)
+    n_layers = args.layers or (max(32, cold_layers) if args.config == "4" else cold_layers)
     n_chunks = (L + B - 1) // B
 
     gen = torch.Generator(device=dev)

@@ -376,6 +376,13 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
   __shared__ __attribute__((aligned(16))) float slots[kShareWaves][kRowsPerWave][kShareSlot];
   __shared__ int any_bad;
   const int tid = threadIdx.x;
+#ifdef SPECEXT_TAIL_STAMPS
+  // profiling build: 100 MHz wall-clock stamps of this workgroup's phases (0 start, 1 parent array there, 2 split
+  // partials and query there, 3 tree K/V rows there, 4 stores issued, 5 stores acknowledged), left in the unused upper
+  // half of the partial-output region, 2 MiB in; the waits that separate 2 and 3 are extra
+  unsigned long long phase_stamp[6];
+  phase_stamp[0] = wall_clock64();
+#endif
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15;
@@ -410,6 +417,10 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
 
   {
     bool bad = false;
+#ifdef SPECEXT_TAIL_STAMPS
+    asm volatile("" :: "v"(par_reg));
+    phase_stamp[1] = wall_clock64();
+#endif
     if (tid < p.T) {
       parent_lds[tid] = par_reg;
       bad = (par_reg >= tid) || (par_reg < -1);
@@ -454,6 +465,12 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
   };
   request_batch();
 
+#ifdef SPECEXT_TAIL_STAMPS
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kAnc) : "memory");      // all but the tree K/V rows, the youngest loads
+  phase_stamp[2] = wall_clock64();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  phase_stamp[3] = wall_clock64();
+#endif
   // the wave's prefix splits: lane i of a group holds (max, sum) of split s_lo + i
   if (!ml_valid || !(ml.y > 0.f)) ml = make_float2(-INFINITY, 0.f);        // an empty split contributes nothing
   float run_max = row16_max(ml.x);
@@ -561,6 +578,18 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
     p.lse2[frow] = l2;
     if (p.lse) p.lse[fh * p.T + ft] = l2 * kLn2;
   }
+#ifdef SPECEXT_TAIL_STAMPS
+  phase_stamp[4] = wall_clock64();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  phase_stamp[5] = wall_clock64();
+  const size_t spare = static_cast<size_t>(p.S) * p.Hq * p.T * D * 2;        // bytes of that upper half
+  if (tid == 0 && spare >= (size_t{2} << 20) + static_cast<size_t>(gridDim.x) * 64) {
+    unsigned long long* st = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(p.part_o) + spare + (2 << 20)) +
+                             blockIdx.x * 8;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) st[i] = phase_stamp[i];
+  }
+#endif
 }
 
 }  // namespace

@@ -8,8 +8,8 @@ Needs the profiling build of the library and one MI355X:
 Runs the Llama-3.1-8B layer shape of the benchmark (60-node tree, 8 layers of distinct K/V so that every launch
 streams from HBM), reads the stamps of the last launch of each pass and prints, in microseconds after the first
 workgroup's start and averaged over the passes: workgroup start, first key tile ready, last key tile done, partial
-stores issued (and, with --merge fused, the phases of the merge tail), the spread between XCDs and the time per
-key tile.  The stamps come from the GPU's 100 MHz wall clock: 10 ns resolution.
+stores issued (and, with --merge fused, the phases of the merge tail; otherwise those of the merge kernel: its data
+arriving and its stores), the spread between XCDs and the time per key tile.  The stamps come from the GPU's 100 MHz wall clock: 10 ns resolution.
 """
 import argparse
 import ctypes
@@ -51,6 +51,11 @@ def main():
     assert off > 0
     n_st = 7 if fused else 4
     acc = []
+    # the merge kernel of the two-launch form (four rows per workgroup) leaves its own stamps 2 MiB further on,
+    # where the spare half of the partial region is large enough
+    n_merge_wg = (Hq * T + 3) // 4
+    merge_fits = S * Hq * T * d * 2 >= (2 << 20) + n_merge_wg * 64
+    merge_acc = []
     for it in range(a.passes + 2):
         for l in range(n_layers):
             sx.verify_attn(buf.desc, q[l], kp[l], vp[l], kt[l], vt[l], parent, buf.out, buf.lse, buf.workspace)
@@ -58,6 +63,10 @@ def main():
         st = buf.workspace[off:off + Hkv * S * 64].view(torch.int64).cpu().numpy().reshape(Hkv, S, 8).astype(np.float64)
         if it >= 2:
             acc.append((st[:, :, :n_st] - st[:, :, 0].min()) / 100.0)
+            if not fused and merge_fits:
+                ms = buf.workspace[off + (2 << 20):off + (2 << 20) + n_merge_wg * 64].view(torch.int64).cpu().numpy()
+                ms = ms.reshape(n_merge_wg, 8)[:, :6].astype(np.float64)
+                merge_acc.append(((ms - ms[:, 0].min()) / 100.0, (ms[:, 0].min() - st[:, :, 3].max()) / 100.0))
     us = np.mean(acc, axis=0)
     names = (["workgroup start", "last key tile done (tail entry)", "own partial acknowledged, flag stored", "tree part done",
               "all flags seen", "own slice merged and written", "done"] if fused else
@@ -72,6 +81,16 @@ def main():
     print("last key tile done, mean per KV head (one head per XCD):", " ".join(f"{us[h, :, last].mean():.2f}" for h in range(Hkv)))
     if not fused:
         print(f"key-tile loop: {np.median(us[:, :, 2] - us[:, :, 1]) / tiles:.3f} us per tile (median workgroup)")
+    if merge_acc:
+        mus = np.mean([a for a, _ in merge_acc], axis=0)
+        gap = np.mean([b for _, b in merge_acc])
+        print(f"merge kernel, {n_merge_wg} workgroups; its first workgroup starts {gap:.2f} us after the prefix kernel's last "
+              "partial store was issued")
+        print(f"{'phase':42s} {'min':>8s} {'median':>8s} {'max':>8s}   (us after the merge kernel's first workgroup's start)")
+        for i, n in enumerate(["workgroup start", "parent array arrived", "split partials and query arrived",
+                               "tree K/V rows arrived", "outputs: stores issued", "outputs: stores acknowledged"]):
+            v = mus[:, i]
+            print(f"{n:42s} {v.min():8.2f} {np.median(v):8.2f} {v.max():8.2f}")
 
 
 if __name__ == "__main__":

@@ -102,16 +102,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void tree_merge_kernel(AttnPar
                                       : reinterpret_cast<const uint32_t*>(p.part_o) + static_cast<int64_t>(row) * D + li * E;
   const int64_t split_words = PART_F16 ? split_stride / 2 : split_stride;
   auto fetch_from = [&](const uint32_t* src, uint32_t (&w)[PW]) {
+    // streaming loads: see tree_merge_shared_kernel
     if constexpr (PW == 4) {
-      const uint4 x = *reinterpret_cast<const uint4*>(src);
-      w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
+      const uintx4 x = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(src));
+      w[0] = x[0]; w[1] = x[1]; w[2] = x[2]; w[3] = x[3];
     } else if constexpr (PW == 8) {
-      const uint4 x = *reinterpret_cast<const uint4*>(src), y = *reinterpret_cast<const uint4*>(src + 4);
-      w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
-      w[4] = y.x; w[5] = y.y; w[6] = y.z; w[7] = y.w;
+      const uintx4 x = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(src));
+      const uintx4 y = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(src + 4));
+      w[0] = x[0]; w[1] = x[1]; w[2] = x[2]; w[3] = x[3];
+      w[4] = y[0]; w[5] = y[1]; w[6] = y[2]; w[7] = y[3];
     } else {
-      const uint2 x = *reinterpret_cast<const uint2*>(src);
-      w[0] = x.x; w[1] = x.y;
+      const uintx2 x = __builtin_nontemporal_load(reinterpret_cast<const uintx2*>(src));
+      w[0] = x[0]; w[1] = x[1];
     }
   };
   auto fetch = [&](int s, uint32_t (&w)[PW]) { fetch_from(po_words + s * split_words, w); };
@@ -404,14 +406,17 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
   // again and count as empty
   const int s_lo = wave * PER;
   const int s_last = p.S - 1;
-  float2 ml = *reinterpret_cast<const float2*>(
-      p.part_ml + (static_cast<int64_t>(min(s_lo + li, s_last)) * n_rows + row) * 2);
+  const floatx2 ml_raw = __builtin_nontemporal_load(reinterpret_cast<const floatx2*>(
+      p.part_ml + (static_cast<int64_t>(min(s_lo + li, s_last)) * n_rows + row) * 2));
+  float2 ml = make_float2(ml_raw[0], ml_raw[1]);
   const bool ml_valid = li < PER && s_lo + li <= s_last;
   const int64_t split_words = static_cast<int64_t>(n_rows) * D / 2;
   const uint32_t* po = reinterpret_cast<const uint32_t*>(p.part_o) + (static_cast<int64_t>(row) * D + li * E) / 2;
   uintx4 raw[PER];
 #pragma unroll
-  for (int u = 0; u < PER; ++u) raw[u] = *reinterpret_cast<const uintx4*>(po + min(s_lo + u, s_last) * split_words);
+  // (streaming loads: partial lines left behind in the L2s would be hit by the next launch's partial stores, which
+  // costs that launch 1.3 - 2 us at prefixes of 2K - 4K tokens, whose K/V stream is too short to evict them first)
+  for (int u = 0; u < PER; ++u) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(po + min(s_lo + u, s_last) * split_words));
   float q[E];
   load_row_part<E, true>(p.q, t * p.q_st + h * p.q_sh + li * E, q);
 

@@ -141,12 +141,12 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
 #pragma unroll
     for (int u = 0; u < kLoadsPerWave; ++u) {
       const int blk = kLoadsPerWave * wave + u;
-      load_to_lds_16(kring_lds + slot + blk * 1024, k_voff[u], kbase + off + blk * 4 * row_bytes);
+      load_to_lds_16_stream(kring_lds + slot + blk * 1024, k_voff[u], kbase + off + blk * 4 * row_bytes);
     }
 #pragma unroll
     for (int u = 0; u < kLoadsPerWave; ++u) {
       const int blk = kLoadsPerWave * wave + u;
-      load_to_lds_16(vring_lds + slot + blk * 1024, v_voff, vbase + off + blk * 4 * row_bytes);
+      load_to_lds_16_stream(vring_lds + slot + blk * 1024, v_voff, vbase + off + blk * 4 * row_bytes);
     }
   };
   // stage s = tiles [s * kStageTiles, (s + 1) * kStageTiles) of the split, cut at n; it

@@ -413,10 +413,11 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
   const int64_t split_words = static_cast<int64_t>(n_rows) * D / 2;
   const uint32_t* po = reinterpret_cast<const uint32_t*>(p.part_o) + (static_cast<int64_t>(row) * D + li * E) / 2;
   uintx4 raw[PER];
-#pragma unroll
   // (streaming loads: partial lines left behind in the L2s would be hit by the next launch's partial stores, which
   // costs that launch 1.3 - 2 us at prefixes of 2K - 4K tokens, whose K/V stream is too short to evict them first)
-  for (int u = 0; u < PER; ++u) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(po + min(s_lo + u, s_last) * split_words));
+  constexpr int kFirst = PER >= 4 ? PER / 2 : PER;      // partials requested before the tree K/V rows
+#pragma unroll
+  for (int u = 0; u < kFirst; ++u) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(po + min(s_lo + u, s_last) * split_words));
   float q[E];
   load_row_part<E, true>(p.q, t * p.q_st + h * p.q_sh + li * E, q);
 
@@ -469,9 +470,12 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
     }
   };
   request_batch();
+  // the rest of the partials goes behind the K/V rows, which would otherwise queue behind all of them
+#pragma unroll
+  for (int u = kFirst; u < PER; ++u) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(po + min(s_lo + u, s_last) * split_words));
 
 #ifdef SPECEXT_TAIL_STAMPS
-  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kAnc) : "memory");      // all but the tree K/V rows, the youngest loads
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kAnc + PER - kFirst) : "memory");      // the loads requested up front
   phase_stamp[2] = wall_clock64();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   phase_stamp[3] = wall_clock64();

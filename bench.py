@@ -45,8 +45,10 @@ def measured_traffic():
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    # 300 steps are 0.3 s of timed work: the first steps behind the synchronisation that opens the timed region run
+    # below the clock the power management settles on, and with 30 steps they are 2 % of the mean
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default 300; 10 for --workload prefill)")
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", choices=["2", "3", "4", "5wide", "5chain", "draft", "draft68m"], default="4",
                     help="numbered workload: 4 (default) = 32 layers at a 16K prefix, the headline metric; 2 / 3 / 5 = "
                          "the single-layer shapes (2K, 8K, 32K-37 with a 128-node wide tree or a 16-node chain), run "
@@ -93,6 +95,8 @@ def parse_args():
 
 def main():
     args = parse_args()
+    if args.steps <= 0:
+        args.steps = 10 if args.workload == "prefill" else 300
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)

@@ -379,9 +379,10 @@ __global__ __launch_bounds__(kShareWaves * 64) void tree_merge_shared_kernel(Att
   __shared__ int any_bad;
   const int tid = threadIdx.x;
 #ifdef SPECEXT_TAIL_STAMPS
-  // profiling build: 100 MHz wall-clock stamps of this workgroup's phases (0 start, 1 parent array there, 2 split
-  // partials and query there, 3 tree K/V rows there, 4 stores issued, 5 stores acknowledged), left in the unused upper
-  // half of the partial-output region, 2 MiB in; the waits that separate 2 and 3 are extra
+  // profiling build: 100 MHz wall-clock stamps of this workgroup's phases (0 start, 1 parent array there, 2 the
+  // partials requested up front and the query there, 3 tree K/V rows and the other partials there, 4 stores issued,
+  // 5 stores acknowledged), left in the unused upper half of the partial-output region, 2 MiB in; the waits that
+  // separate 2 and 3 are extra
   unsigned long long phase_stamp[6];
   phase_stamp[0] = wall_clock64();
 #endif

@@ -87,8 +87,9 @@ def main():
         print(f"merge kernel, {n_merge_wg} workgroups; its first workgroup starts {gap:.2f} us after the prefix kernel's last "
               "partial store was issued")
         print(f"{'phase':42s} {'min':>8s} {'median':>8s} {'max':>8s}   (us after the merge kernel's first workgroup's start)")
-        for i, n in enumerate(["workgroup start", "parent array arrived", "split partials and query arrived",
-                               "tree K/V rows arrived", "outputs: stores issued", "outputs: stores acknowledged"]):
+        for i, n in enumerate(["workgroup start", "parent array arrived", "first half of the partials, query arrived",
+                               "tree K/V rows, other partials arrived", "outputs: stores issued",
+                               "outputs: stores acknowledged"]):
             v = mus[:, i]
             print(f"{n:42s} {v.min():8.2f} {np.median(v):8.2f} {v.max():8.2f}")
 

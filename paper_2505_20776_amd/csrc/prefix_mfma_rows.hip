@@ -45,17 +45,22 @@ constexpr int kTileBytes = kTile * kRowBytes;     // 8 KB
 #define SPECEXT_ROWS_STAGES 4
 #endif
 constexpr int kStageTiles = SPECEXT_ROWS_STAGE_TILES;   // tiles between two workgroup barriers
-constexpr int kStages = SPECEXT_ROWS_STAGES;            // stages per ring (>= 2)
-constexpr int kRing = kStageTiles * kStages;            // tiles per ring (K ring and V ring)
-constexpr int kRingBytes = 2 * kRing * kTileBytes;
+// Stages per ring (>= 2), a template parameter of the kernel.  The deep ring is for long splits; a split of few tiles
+// (a workgroup of eight waves only) takes a ring of two stages: measured 0.5 - 0.9 us shorter per launch up to 16 tiles
+// per split, equal at 32, 1 - 2 % longer at 64 and more (and much longer with four waves, whose tiles are consumed
+// faster than one tile of look-ahead arrives).
+constexpr int kDeepStages = SPECEXT_ROWS_STAGES;
+constexpr int kShortStages = 2;
+constexpr int kShortSplitTiles = 24;                    // splits of at most this many tiles take the short ring
+constexpr int ring_bytes(int stages) { return 2 * kStageTiles * stages * kTileBytes; }
 // Behind the rings every wave has a private area: first the staging of its 32 query
 // rows (32 x 256 B), at the end the staging of its 32 partial output rows as fp16
 // (rows padded to 264 B so that the 8-byte column writes fall into distinct banks).
 constexpr int kPatchStride = kRowBytes + 8;
 constexpr int kPrivBytes = 32 * kPatchStride;
 // Behind those, the area of the fused tree-pass / merge tail (parent[], control words, tree slots).
-constexpr int lds_bytes(int waves) { return kRingBytes + waves * kPrivBytes + tail_private_bytes(waves * 64); }
-static_assert(kStages >= 2 && lds_bytes(8) <= 160 * 1024, "rings and private areas must fit the 160 KB of LDS");
+constexpr int lds_bytes(int waves, int stages) { return ring_bytes(stages) + waves * kPrivBytes + tail_private_bytes(waves * 64); }
+static_assert(kDeepStages >= 2 && lds_bytes(8, kDeepStages) <= 160 * 1024, "rings and private areas must fit the 160 KB of LDS");
 
 template <int I>
 using ic = std::integral_constant<int, I>;
@@ -74,9 +79,12 @@ __device__ __forceinline__ void static_for(F&& f) {
 // even and of the odd keys of the rows come from the first and the second half of the
 // K fragments against the same four query fragments, and the even / odd probabilities
 // meet V^T's first / second pair of 32-column blocks in the same two output blocks.
-template <int WAVES, bool SCORES, int KPR>
+template <int WAVES, bool SCORES, int KPR, int STAGES>
 __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int kStages = STAGES;
+  constexpr int kRing = kStageTiles * kStages;            // tiles per ring (K ring and V ring)
+  constexpr int kRingBytes = ring_bytes(kStages);
   constexpr int kLoadsPerWave = 8 / WAVES;       // 1 KB blocks of a tile that one wave fills (per K or V)
   constexpr int kKeysPerTile = kTile * KPR;
   constexpr int kQSteps = 8 / KPR;               // 16-wide contraction steps of one query row
@@ -537,10 +545,10 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   }
 }
 
-template <int WAVES, bool SCORES, int KPR>
+template <int WAVES, bool SCORES, int KPR, int STAGES = kDeepStages>
 hipError_t launch_rows(const AttnParams& p, hipStream_t stream) {
-  auto kernel = prefix_rows_kernel<WAVES, SCORES, KPR>;
-  constexpr int kLdsBytes = lds_bytes(WAVES);
+  auto kernel = prefix_rows_kernel<WAVES, SCORES, KPR, STAGES>;
+  constexpr int kLdsBytes = lds_bytes(WAVES, STAGES);
   if (kLdsBytes > 64 * 1024) {
     // more than the default 64 KB of dynamic LDS: raise the cap once per device
     static std::atomic<bool> attr_set[64];
@@ -568,7 +576,12 @@ hipError_t launch_prefix_mfma_rows(const AttnParams& p, hipStream_t stream) {
     if (big) return p.want_scores ? launch_rows<8, true, 2>(p, stream) : launch_rows<8, false, 2>(p, stream);
     return p.want_scores ? launch_rows<4, true, 2>(p, stream) : launch_rows<4, false, 2>(p, stream);
   }
-  if (big) return p.want_scores ? launch_rows<8, true, 1>(p, stream) : launch_rows<8, false, 1>(p, stream);
+  if (big) {
+    const int split_tiles = (p.keys_per_split + kTile - 1) / kTile;
+    if (split_tiles <= kShortSplitTiles)
+      return p.want_scores ? launch_rows<8, true, 1, kShortStages>(p, stream) : launch_rows<8, false, 1, kShortStages>(p, stream);
+    return p.want_scores ? launch_rows<8, true, 1>(p, stream) : launch_rows<8, false, 1>(p, stream);
+  }
   return p.want_scores ? launch_rows<4, true, 1>(p, stream) : launch_rows<4, false, 1>(p, stream);
 }
 

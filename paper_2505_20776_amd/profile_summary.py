@@ -107,7 +107,7 @@ def main():
     sp = sub.add_parser("traffic")
     sp.add_argument("fetch_db")
     sp.add_argument("write_db")
-    sp.add_argument("--kernel", default="prefix_rows_kernel<8, false, 1>")
+    sp.add_argument("--kernel", default="prefix_rows_kernel<8, false, 1, ")
     sp.add_argument("--copy-kernel", default="gather_copy_kernel")
     sp.add_argument("--copy-kib", type=float, default=4096.0)
     sp.add_argument("--out", default="")

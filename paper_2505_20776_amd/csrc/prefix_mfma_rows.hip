@@ -101,6 +101,22 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   // done, 3 partial stores issued (the fused tail, when it runs, overwrites 1.. with its own phases)
   const unsigned long long stamp_start = wall_clock64();
   unsigned long long stamp_first = 0, stamp_loop = 0;
+  // and, per wave, shader-clock stamps inside the key loop (low 32 bits of s_memtime) for the 16 tiles from
+  // kLoopStampTile0 on: 0 this wave's loads of the tile have arrived, 1 behind the barrier, 2 between the two
+  // halves of the loop order (before the second product in the rotated order, before the softmax otherwise),
+  // 3 the tile's last instruction issued.  Lane 4 * (tile - kLoopStampTile0) + k of loop_stamps holds stamp k.
+  constexpr int kLoopStampTile0 = 4;
+  int loop_stamps = 0;
+  unsigned long long ls_arrived = 0, ls_barrier = 0, ls_half = 0, ls_end = 0;
+  const unsigned long long ls_begin = __builtin_amdgcn_s_memtime();
+#define SPECEXT_LOOP_STAMP(var)              \
+  do {                                       \
+    __builtin_amdgcn_sched_barrier(0);       \
+    var = __builtin_amdgcn_s_memtime();      \
+    __builtin_amdgcn_sched_barrier(0);       \
+  } while (0)
+#else
+#define SPECEXT_LOOP_STAMP(var) do { } while (0)
 #endif
 
   const int split = p.head_fastest ? blockIdx.y : blockIdx.x;
@@ -422,7 +438,9 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
           } else {
             wait_vmcnt_even(younger_than_stage(s));
           }
+          SPECEXT_LOOP_STAMP(ls_arrived);
           lds_barrier();
+          SPECEXT_LOOP_STAMP(ls_barrier);
 #ifdef SPECEXT_TAIL_STAMPS
           if (s == 0) stamp_first = wall_clock64();
 #endif
@@ -434,15 +452,34 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
               if constexpr (kOrder == 2) {
                 if (j > 0) tile_second_product();
                 tile_front(ic<u * kStageTiles + i>{});
+                SPECEXT_LOOP_STAMP(ls_half);
                 tile_softmax(j);
               } else if constexpr (kRot) {
-                if (j > 0) tile_back(j - 1);
+                if (j > 0) tile_softmax(j - 1);
+                SPECEXT_LOOP_STAMP(ls_half);
+                if (j > 0) tile_second_product();
                 tile_front(ic<u * kStageTiles + i>{});
               } else {
                 tile_front(ic<u * kStageTiles + i>{});
+                SPECEXT_LOOP_STAMP(ls_half);
                 tile_back(j);
               }
             }
+#ifdef SPECEXT_TAIL_STAMPS
+            SPECEXT_LOOP_STAMP(ls_end);
+            if (j >= kLoopStampTile0 && j < kLoopStampTile0 + 16) {
+              // (plain copies: operands of inline assembly alone are not captured by the enclosing lambdas)
+              int reg = loop_stamps;
+              const int at = 4 * (j - kLoopStampTile0);
+              const int t0 = static_cast<int>(ls_arrived), t1 = static_cast<int>(ls_barrier), t2 = static_cast<int>(ls_half),
+                        t3 = static_cast<int>(ls_end);
+              asm volatile("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(reg) : "s"(t0), "s"(at) : "m0");
+              asm volatile("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(reg) : "s"(t1), "s"(at + 1) : "m0");
+              asm volatile("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(reg) : "s"(t2), "s"(at + 2) : "m0");
+              asm volatile("s_mov_b32 m0, %2\n\tv_writelane_b32 %0, %1, m0" : "+v"(reg) : "s"(t3), "s"(at + 3) : "m0");
+              loop_stamps = reg;
+            }
+#endif
           });
         }
       });
@@ -529,6 +566,25 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_rows_kernel(AttnParams p) {
   }
   }
 #ifdef SPECEXT_TAIL_STAMPS
+  if (KPR == 1 && WAVES == 8) {
+    // the loop stamps of every wave: 80 words per wave, 4 MiB into the spare half of the partial region (when
+    // that half reaches so far): words 0..63 the register above, 64 / 65 the shader-clock counter at the kernel's
+    // start and here, 66 / 67 the 100 MHz wall clock at the same two points
+    const size_t spare = static_cast<size_t>(p.S) * p.Hq * p.T * kD * 2;
+    const size_t n_wg = static_cast<size_t>(gridDim.x) * gridDim.y * gridDim.z;
+    if (spare >= (4u << 20) + n_wg * WAVES * 80 * 4) {
+      const unsigned long long ls_done = __builtin_amdgcn_s_memtime();
+      int* st = reinterpret_cast<int*>(reinterpret_cast<unsigned char*>(p.part_o) + spare + (4u << 20)) +
+                ((((blockIdx.z * p.Hkv + g) * p.S + split) * WAVES + wave) * 80);
+      st[lane] = loop_stamps;
+      if (lane == 0) {
+        st[64] = static_cast<int>(ls_begin);
+        st[65] = static_cast<int>(ls_done);
+        st[66] = static_cast<int>(stamp_start);
+        st[67] = static_cast<int>(wall_clock64());
+      }
+    }
+  }
   if (KPR == 1 && threadIdx.x == 0) {
     unsigned long long* st = reinterpret_cast<unsigned long long*>(reinterpret_cast<unsigned char*>(p.part_o) +
                                                                    static_cast<size_t>(p.S) * p.Hq * p.T * kD * 2) +

@@ -82,6 +82,9 @@ def parse_args():
     ap.add_argument("--hold-what", choices=["stream", "mfma", "prefix", "step"], default="step",
                     help="stream: the HBM read calibration kernel; mfma: the matrix-core calibration kernel; prefix: "
                          "the prefix-pass kernel alone over all layers; step: whole verification steps")
+    ap.add_argument("--issue-probe", action="store_true",
+                    help="instead of the benchmark: time the library's probe of how matrix and vector instructions share "
+                         "a SIMD (specext_calib_issue_mix) and print one JSON line")
     ap.add_argument("--no-calibrate", action="store_true",
                     help="skip the two calibration kernels (pure HBM read stream, pure bf16 matrix-core loop) whose rates "
                          "are reported as measured_* next to the published peaks")
@@ -231,6 +234,8 @@ def main():
             run_step()
         stream.synchronize()
 
+        if args.issue_probe:
+            return issue_probe(sx, event_time_us)
         if args.hold > 0:
             return hold(args, sx, torch, stream, run_step, run_prefix, n_layers, layer_bytes,
                         4.0 * d * T * (Hq // Hkv) * Hkv * L)
@@ -397,6 +402,21 @@ def hold(args, sx, torch, stream, run_step, run_prefix, n_layers, layer_bytes, l
         per = us / n_layers if args.hold_what == "prefix" else us / n_layers
         out.update({"us_per_layer": round(per, 2), "GBps": round(layer_bytes / per / 1e3, 1),
                     "TFLOPs": round(layer_flops / per / 1e6, 1)})
+    print(json.dumps(out))
+
+
+def issue_probe(sx, event_time_us):
+    """How the matrix and the vector instructions of the two waves of a SIMD share it: 256 workgroups of eight waves
+    (w and w + 4 on one SIMD), 2000 iterations of 16 matrix instructions and / or 16 x n vector instructions per wave."""
+    iters, wgs = 2000, 256
+    out = {"issue_probe": "specext_calib_issue_mix", "iters": iters, "workgroups": wgs, "us": {}}
+    for n in (4, 8):
+        for mode, name in ((1, "matrix_waves_alone"), (2, "vector_waves_alone"), (3, "matrix_waves_and_vector_waves")):
+            if mode == 1 and n == 8:
+                continue
+            out["us"][f"{name}_n{n}"] = round(event_time_us(lambda: sx.calib_issue_mix(mode, n, iters, wgs), 5), 1)
+    for n in (0, 4, 8):
+        out["us"][f"all_waves_in_turns_n{n}"] = round(event_time_us(lambda: sx.calib_issue_mix(4, n, iters, wgs), 5), 1)
     print(json.dumps(out))
 
 

@@ -420,9 +420,21 @@ int specext_num_splits(const specext_desc* desc);
  *   tile = 16: v_mfma_f32_16x16x32_bf16) on register operands of roughly unit variance
  *   and nothing else.  Returns the number of floating-point operations of the launch
  *   (> 0), or a negative specext_status.  sink: device float [1] or NULL.
+ * specext_calib_issue_mix: how matrix and vector instructions share a SIMD (what bounds the
+ *   tile loop of the prefix pass, whose every tile is 16 matrix instructions and some 70
+ *   vector instructions per wavefront, two wavefronts per SIMD).  `workgroups` workgroups of
+ *   eight wavefronts, wavefronts w and w + 4 on one SIMD; per iteration a wavefront issues 16
+ *   v_mfma_f32_32x32x16_bf16, or 16 x vector_per_matrix vector instructions (three fused
+ *   multiply-adds and one exponential in every four), or both in turns.  mode 1: wavefronts
+ *   0..3 matrix only (the others leave at once); 2: wavefronts 4..7 vector only; 3: both of
+ *   these together; 4: all eight wavefronts, one matrix instruction then vector_per_matrix
+ *   vector ones.  vector_per_matrix: 0, 4 or 8.  Time it with events on `stream`.  Returns
+ *   SPECEXT_OK or a negative specext_status; nothing is launched on an error.
  */
 int specext_calib_stream_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
 int64_t specext_calib_mfma(int32_t iters, int32_t tile, int32_t workgroups, float* sink, void* stream);
+int specext_calib_issue_mix(int32_t mode, int32_t vector_per_matrix, int32_t iters, int32_t workgroups, float* sink,
+                            void* stream);
 
 #ifdef __cplusplus
 }

@@ -34,7 +34,7 @@ EXPORTED = ("specext_strerror", "specext_workspace_bytes", "specext_num_splits",
             "specext_commit_tree_kv", "specext_chunk_scores_accepted", "specext_materialized_bytes",
             "specext_materialized_ld", "specext_attn_materialized", "specext_chunk_scores_materialized",
             "specext_prefill_attn", "specext_verify_attn_static", "specext_workspace_init",
-            "specext_calib_stream_read", "specext_calib_mfma", "specext_chunk_scores_select")
+            "specext_calib_stream_read", "specext_calib_mfma", "specext_calib_issue_mix", "specext_chunk_scores_select")
 
 
 class SpecextError(RuntimeError):
@@ -114,6 +114,8 @@ def load_library() -> ctypes.CDLL:
     lib.specext_calib_stream_read.argtypes = [vp, sz, vp, vp]
     lib.specext_calib_mfma.restype = ctypes.c_int64
     lib.specext_calib_mfma.argtypes = [i32, i32, i32, vp, vp]
+    lib.specext_calib_issue_mix.restype = ctypes.c_int
+    lib.specext_calib_issue_mix.argtypes = [i32, i32, i32, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -330,6 +332,15 @@ def calib_mfma(iters: int, tile: int = 32, workgroups: int = 512, sink=None, str
                                                     _stream(stream)))
     if check and rc < 0:
         _check(rc, "specext_calib_mfma")
+    return rc
+
+
+def calib_issue_mix(mode: int, vector_per_matrix: int, iters: int, workgroups: int = 256, sink=None, stream=None,
+                    check: bool = True) -> int:
+    rc = int(load_library().specext_calib_issue_mix(int(mode), int(vector_per_matrix), int(iters), int(workgroups),
+                                                    _ptr(sink), _stream(stream)))
+    if check:
+        _check(rc, "specext_calib_issue_mix")
     return rc
 
 

@@ -1,6 +1,7 @@
 // Measurement aids (not part of the method): what this GPU sustains in a pure HBM read
 // stream and in pure dense bf16 matrix-core work, so that a benchmark can quote the
-// verification kernels against measured ceilings next to the published ones.
+// verification kernels against measured ceilings next to the published ones; and how the
+// matrix and the vector instructions of the two waves of a SIMD share it.
 #include "mfma_util.h"
 
 namespace specext {
@@ -86,6 +87,64 @@ __global__ __launch_bounds__(256) void calib_mfma_kernel(int iters, float* sink)
   if (total == 12345.678f && sink) sink[0] = total;
 }
 
+// How matrix and vector instructions share one SIMD.  A workgroup of eight waves puts waves w and w + 4 on one
+// SIMD; per loop iteration a wave issues 16 matrix instructions (four independent accumulators), 16 x NV vector
+// instructions (three fused multiply-adds and one exponential in every four, on registers of its own), or both in
+// turns: one matrix instruction, then NV vector ones.
+//   mode 1: waves 0..3 matrix only, waves 4..7 leave        mode 2: waves 4..7 vector only, waves 0..3 leave
+//   mode 3: waves 0..3 matrix only, waves 4..7 vector only  mode 4: all eight waves, matrix and vector in turns
+template <int NV, bool MATRIX, bool VECTOR>
+__device__ __forceinline__ float issue_loop(uint32_t seed, int iters) {
+  const bf16x8 a = operand_of(seed + 17u), b = operand_of(seed + 101u);
+  floatx16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = static_cast<float>((seed >> (3 * i)) & 255u) * (1.0f / 512.0f);
+  const float c = 0.9999f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      if constexpr (MATRIX) {
+        acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[u & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (VECTOR) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+          float& x = v[(u + q) & 7];
+          x = (q & 3) == 3 ? fast_exp2(-x) : fmaf(x, c, 0.001f);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+  float total = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) total += v[i];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) total += acc[i][r];
+  return total;
+}
+
+template <int NV>
+__global__ __launch_bounds__(512) void calib_issue_kernel(int mode, int iters, float* sink) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool upper = wave >= 4;
+  if ((mode == 1 && upper) || (mode == 2 && !upper)) return;
+  const uint32_t seed = (blockIdx.x * 512u + threadIdx.x) * 2654435761u;
+  float total;
+  if (mode == 4) total = issue_loop<NV, true, true>(seed, iters);
+  else if (upper) total = issue_loop<NV, false, true>(seed, iters);
+  else total = issue_loop<NV, true, false>(seed, iters);
+  if (total == 12345.678f && sink) sink[0] = total;
+}
+
 }  // namespace
 }  // namespace specext
 
@@ -114,6 +173,20 @@ int64_t specext_calib_mfma(int32_t iters, int32_t tile, int32_t workgroups, floa
   // floating-point operations of the launch: workgroups x 4 waves x iters x 16 products
   const int64_t per_product = tile == 32 ? 2LL * 32 * 32 * 16 : 2LL * 16 * 16 * 32;
   return static_cast<int64_t>(workgroups) * 4 * iters * 16 * per_product;
+}
+
+int specext_calib_issue_mix(int32_t mode, int32_t vector_per_matrix, int32_t iters, int32_t workgroups, float* sink,
+                            void* stream) {
+  if (mode < 1 || mode > 4 || iters <= 0 || workgroups <= 0) return SPECEXT_ERR_INVALID_ARG;
+  if (iters > (1 << 24) || workgroups > (1 << 16)) return SPECEXT_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  switch (vector_per_matrix) {
+    case 0: calib_issue_kernel<0><<<workgroups, 512, 0, s>>>(mode, iters, sink); break;
+    case 4: calib_issue_kernel<4><<<workgroups, 512, 0, s>>>(mode, iters, sink); break;
+    case 8: calib_issue_kernel<8><<<workgroups, 512, 0, s>>>(mode, iters, sink); break;
+    default: return SPECEXT_ERR_UNSUPPORTED;
+  }
+  return hipGetLastError() == hipSuccess ? SPECEXT_OK : SPECEXT_ERR_LAUNCH_FAILED;
 }
 
 }  // extern "C"

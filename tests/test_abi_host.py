@@ -184,3 +184,18 @@ def test_prefill_argument_checks(sx):
     assert sx.prefill_attn(a, a, a, a, None, **dict(base, q_len=8, kv_len=16)) == -2   # under one tile of keys
     assert sx.prefill_attn(a + 2, a, a, a, None, **base) == -2
     assert sx.prefill_attn(a, a, a, a, None, **dict(base, kv_stride_l=100)) == -2
+
+
+def test_calibration_argument_checks(sx):
+    """The measurement aids refuse bad arguments before anything is launched (no GPU is touched)."""
+    lib = sx.load_library()
+    mix = lambda mode, n, iters, wgs: lib.specext_calib_issue_mix(mode, n, iters, wgs, None, None)
+    bad = [mix(0, 4, 10, 1), mix(5, 4, 10, 1), mix(1, 4, 0, 1), mix(1, 4, 10, 0)]
+    assert all(rc < 0 for rc in bad) and len(set(bad)) == 1
+    invalid = bad[0]
+    unsupported = mix(1, 3, 10, 1)          # vector instructions per matrix one: 0, 4 or 8
+    assert unsupported < 0 and unsupported != invalid
+    assert mix(1, 4, (1 << 24) + 1, 1) == unsupported
+    assert lib.specext_calib_mfma(0, 32, 1, None, None) == invalid
+    assert lib.specext_calib_mfma(10, 24, 1, None, None) == invalid
+    assert lib.specext_calib_stream_read(None, 32768, None, None) == invalid
